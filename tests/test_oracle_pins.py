@@ -1,0 +1,286 @@
+"""Pins for the fp64 CPU oracle: it is checked here against things other than itself.
+
+* literal Eq. 3 (no max subtraction, explicit sums) in pure Python on tiny inputs;
+* softmax rows summing to one;
+* closed forms (Q = 0, one-hot V, constant V, row 0, a two-key hand example);
+* a library attention routine (torch SDPA, CPU, fp64, explicit boolean mask);
+* chunk-split / merge-order invariance, merge identity, GQA = MHA with repeated
+  KV heads, varlen = per-sequence dense.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as oracle
+from paper_2409_15104_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def brute_force(q, k, v, q_off, kv_off, causal, scale):
+    """Eq. 2-3 spelled out with Python floats: b_ij = exp(a_ij) / sum_{k<=t_i} exp(a_ik)."""
+    sq, hq, d = q.shape
+    sk, hkv, _ = k.shape
+    g = hq // hkv
+    out = [[[0.0] * d for _ in range(hq)] for _ in range(sq)]
+    lse = [[-math.inf] * sq for _ in range(hq)]
+    for i in range(sq):
+        t_i = q_off + i  # global index of the token on row i
+        for h in range(hq):
+            kvh = h // g
+            e = []
+            for j in range(sk):
+                if causal and kv_off + j > t_i:
+                    e.append(None)
+                    continue
+                a = sum(float(q[i, h, c]) * float(k[j, kvh, c]) for c in range(d)) * scale
+                e.append(math.exp(a))
+            den = sum(x for x in e if x is not None)
+            if den == 0.0:
+                continue
+            for j in range(sk):
+                if e[j] is None:
+                    continue
+                b = e[j] / den
+                for c in range(d):
+                    out[i][h][c] += b * float(v[j, kvh, c])
+            lse[h][i] = math.log(den)
+    return np.array(out), np.array(lse)
+
+
+@pytest.mark.parametrize("sq,sk,hq,hkv,d,q_off,kv_off,causal", [
+    (5, 5, 2, 2, 4, 0, 0, True),
+    (5, 5, 2, 1, 4, 0, 0, False),
+    (4, 7, 4, 2, 3, 6, 2, True),    # rectangular, GQA, all rows see several keys
+    (6, 4, 2, 1, 2, 1, 3, True),    # first rows see nothing (future chunk start)
+    (3, 8, 6, 2, 4, 0, 5, True),    # wholly future chunk
+    (8, 3, 1, 1, 1, 10, 0, True),   # wholly past chunk: no masking at all
+])
+def test_matches_literal_eq3(sq, sk, hq, hkv, d, q_off, kv_off, causal):
+    q = _rand((sq, hq, d), 1)
+    k = _rand((sk, hkv, d), 2)
+    v = _rand((sk, hkv, d), 3)
+    scale = 1.0 / math.sqrt(d)
+    o_ref, l_ref = brute_force(q, k, v, q_off, kv_off, causal, scale)
+    o, lse = oracle.attention(q, k, v, q_off=q_off, kv_off=kv_off, causal=causal)
+    np.testing.assert_allclose(o, o_ref, rtol=0, atol=1e-12)
+    fin = np.isfinite(l_ref)
+    assert np.array_equal(np.isfinite(lse), fin)
+    np.testing.assert_allclose(lse[fin], l_ref[fin], rtol=0, atol=1e-12)
+    assert np.all(lse[~fin] == -np.inf)
+    assert np.all(o[np.transpose(~fin)] == 0.0)
+
+
+def test_softmax_rows_sum_to_one():
+    q = _rand((17, 4, 8), 4)
+    k = _rand((23, 2, 8), 5)
+    v = _rand((23, 2, 8), 6)
+    _, lse, p = oracle.attention(q, k, v, q_off=9, kv_off=3, causal=True, return_probs=True)
+    rows = p.sum(axis=-1)
+    np.testing.assert_allclose(rows[np.isfinite(lse)], 1.0, rtol=0, atol=1e-12)
+    # weights of masked keys are exactly zero, visible ones strictly positive
+    for i in range(17):
+        n_i = min(max(9 + i - 3 + 1, 0), 23)
+        assert np.all(p[:, i, n_i:] == 0.0)
+        assert np.all(p[:, i, :n_i] > 0.0)
+
+
+def test_two_key_hand_example():
+    """tests/golden/two_key_example.txt: scores ln 1 and ln 3 give weights 1/4 and 3/4."""
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "two_key_example.txt")) if ln.strip() and ln[0] != "#"]
+    vals = {r[0]: [float(x) for x in r[1:]] for r in rows}
+    q = np.array(vals["q"]).reshape(1, 1, 1)
+    k = np.array(vals["k"]).reshape(2, 1, 1)
+    v = np.array(vals["v"]).reshape(2, 1, 1)
+    o, lse = oracle.attention(q, k, v, q_off=1, kv_off=0, causal=True, scale=1.0)
+    assert abs(o[0, 0, 0] - vals["o"][0]) < 1e-14
+    assert abs(lse[0, 0] - vals["lse"][0]) < 1e-14
+    # the same row one position earlier sees only key 0
+    o, lse = oracle.attention(q, k, v, q_off=0, kv_off=0, causal=True, scale=1.0)
+    assert o[0, 0, 0] == vals["v"][0] and lse[0, 0] == 0.0
+
+
+@pytest.mark.parametrize("q_off,kv_off,sq,sk", [(0, 0, 40, 40), (100, 37, 33, 90), (5, 20, 30, 9), (0, 64, 16, 16)])
+def test_zero_query_counts_visible_keys(q_off, kv_off, sq, sk):
+    """Q = 0: every visible key weighs 1/n_i, so LSE_i = ln n_i and O_i = mean of visible V."""
+    hq, hkv, d = 4, 2, 8
+    q = np.zeros((sq, hq, d))
+    k = _rand((sk, hkv, d), 7)
+    v = _rand((sk, hkv, d), 8)
+    o, lse = oracle.attention(q, k, v, q_off=q_off, kv_off=kv_off, causal=True)
+    for i in range(sq):
+        n_i = min(max(q_off + i - kv_off + 1, 0), sk)
+        for h in range(hq):
+            if n_i == 0:
+                assert lse[h, i] == -np.inf and np.all(o[i, h] == 0.0)
+            else:
+                assert round(math.exp(lse[h, i])) == n_i
+                np.testing.assert_allclose(o[i, h], v[:n_i, h // 2].mean(axis=0), rtol=0, atol=1e-13)
+
+
+def test_one_hot_value_exposes_the_mask_exactly():
+    sq, sk, d = 12, 12, 4
+    for jstar in (0, 5, 11):
+        v = np.zeros((sk, 1, d))
+        v[jstar, 0, :] = 1.0
+        o, _ = oracle.attention(np.zeros((sq, 1, d)), _rand((sk, 1, d), 9), v, q_off=0, kv_off=0, causal=True)
+        for i in range(sq):
+            expect = 1.0 / (i + 1) if jstar <= i else 0.0
+            assert abs(o[i, 0, 0] - expect) < 1e-15
+            if jstar > i:
+                assert o[i, 0, 0] == 0.0
+
+
+def test_row_zero_and_constant_value():
+    q, k, v = (_rand((9, 2, 16), s) for s in (10, 11, 12))
+    o, lse = oracle.attention(q, k, v, causal=True)
+    np.testing.assert_allclose(o[0], v[0], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(lse[:, 0], (q[0] * k[0]).sum(-1) / 4.0, rtol=0, atol=1e-14)
+    vc = np.full_like(v, -2.5)
+    o, _ = oracle.attention(q, k, vc, causal=True)
+    np.testing.assert_allclose(o, -2.5, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_against_library_sdpa_fp64(causal):
+    sq, sk, hq, hkv, d, q_off, kv_off = 37, 61, 6, 2, 32, 40, 7
+    q, k, v = _rand((sq, hq, d), 13), _rand((sk, hkv, d), 14), _rand((sk, hkv, d), 15)
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]                        # [1, Hq, sq, d]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(hq // hkv, 0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(hq // hkv, 0)[None]
+    if causal:
+        mask = (kv_off + torch.arange(sk))[None, :] <= (q_off + torch.arange(sq))[:, None]
+    else:
+        mask = torch.ones(sq, sk, dtype=torch.bool)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)[0].permute(1, 0, 2).numpy()
+    o, lse = oracle.attention(q, k, v, q_off=q_off, kv_off=kv_off, causal=causal)
+    np.testing.assert_allclose(o, ref, rtol=0, atol=1e-10)
+    # LSE against torch.logsumexp of the masked scaled scores
+    s = torch.einsum("hid,hjd->hij", tq[0], tk[0]) / math.sqrt(d)
+    s = s.masked_fill(~mask, -math.inf)
+    np.testing.assert_allclose(lse, torch.logsumexp(s, dim=-1).numpy(), rtol=0, atol=1e-10)
+
+
+def test_bf16_bits_are_widened_exactly():
+    q, k, v = synth.qkv(21, 19, 27, 4, 2, d=16)
+    o16, l16 = oracle.attention(q, k, v, q_off=8, kv_off=0, causal=True)
+    o64, l64 = oracle.attention(q.double().numpy(), k.double().numpy(), v.double().numpy(), q_off=8, kv_off=0)
+    assert np.array_equal(o16, o64) and np.array_equal(l16, l64)
+
+
+def _split_points(rng, n, parts):
+    cuts = sorted(rng.integers(0, n + 1, size=parts - 1).tolist())
+    return [0] + cuts + [n]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_chunked_then_merged_equals_unchunked(seed):
+    rng = np.random.default_rng(100 + seed)
+    sq, sk, hq, hkv, d = 21, 50, 4, 2, 8
+    q_off = int(rng.integers(0, 50))
+    q, k, v = _rand((sq, hq, d), 16 + seed), _rand((sk, hkv, d), 17 + seed), _rand((sk, hkv, d), 18 + seed)
+    o_full, l_full = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
+    edges = _split_points(rng, sk, int(rng.integers(2, 7)))          # uneven, may hold empty chunks
+    parts = [oracle.attention(q, k[a:b], v[a:b], q_off=q_off, kv_off=a, causal=True) for a, b in zip(edges, edges[1:])]
+    order = rng.permutation(len(parts))
+    o, lse = np.zeros_like(o_full), np.full_like(l_full, -np.inf)
+    for idx in order:                                                  # left fold in a random order
+        o, lse = oracle.merge(o, lse, *parts[idx])
+    np.testing.assert_allclose(o, o_full, rtol=0, atol=1e-12)
+    fin = np.isfinite(l_full)
+    assert np.array_equal(np.isfinite(lse), fin)
+    np.testing.assert_allclose(lse[fin], l_full[fin], rtol=0, atol=1e-12)
+    # a balanced tree gives the same answer
+    level = [parts[i] for i in order]
+    while len(level) > 1:
+        nxt = [oracle.merge(*level[i], *level[i + 1]) for i in range(0, len(level) - 1, 2)]
+        if len(level) % 2:
+            nxt.append(level[-1])
+        level = nxt
+    np.testing.assert_allclose(level[0][0], o_full, rtol=0, atol=1e-12)
+
+
+def test_merge_identity_and_symmetry():
+    o_a, o_b = _rand((7, 3, 5), 30), _rand((7, 3, 5), 31)
+    l_a, l_b = _rand((3, 7), 32), _rand((3, 7), 33)
+    zero, ninf = np.zeros_like(o_a), np.full_like(l_a, -np.inf)
+    o, lse = oracle.merge(o_a, l_a, zero, ninf)
+    assert np.array_equal(o, o_a) and np.array_equal(lse, l_a)
+    o, lse = oracle.merge(zero, ninf, o_a, l_a)
+    assert np.array_equal(o, o_a) and np.array_equal(lse, l_a)
+    o, lse = oracle.merge(zero, ninf, zero, ninf)
+    assert np.all(o == 0.0) and np.all(lse == -np.inf)
+    o1, l1 = oracle.merge(o_a, l_a, o_b, l_b)
+    o2, l2 = oracle.merge(o_b, l_b, o_a, l_a)
+    np.testing.assert_allclose(o1, o2, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(l1, l2, rtol=0, atol=1e-15)
+    # textbook value: equal LSEs average the two outputs and add ln 2
+    o, lse = oracle.merge(o_a, l_a, o_b, l_a)
+    np.testing.assert_allclose(o, 0.5 * (o_a + o_b), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(lse, l_a + math.log(2.0), rtol=0, atol=1e-15)
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    q, k, v = _rand((11, 8, 8), 40), _rand((13, 2, 8), 41), _rand((13, 2, 8), 42)
+    o_g, l_g = oracle.attention(q, k, v, q_off=4, kv_off=0)
+    o_m, l_m = oracle.attention(q, np.repeat(k, 4, axis=1), np.repeat(v, 4, axis=1), q_off=4, kv_off=0)
+    assert np.array_equal(o_g, o_m) and np.array_equal(l_g, l_m)
+
+
+def test_ring_schedule_and_sp_prefill():
+    assert oracle.ring_schedule(2, 4) == [2, 1, 0]
+    assert oracle.ring_schedule(0, 4) == [0]
+    assert oracle.ring_schedule(1, 4, causal=False) == [1, 0, 3, 2]
+    sq, s, hq, hkv, d, chunk = 10, 47, 4, 2, 8, 10                     # last chunk is short (7 tokens)
+    q_all, k, v = _rand((s, hq, d), 50), _rand((s, hkv, d), 51), _rand((s, hkv, d), 52)
+    o_full, l_full = oracle.attention(q_all, k, v, causal=True)
+    for r in range(5):
+        lo, hi = r * chunk, min(s, (r + 1) * chunk)
+        o, lse = oracle.sp_prefill(q_all[lo:hi], k, v, q_off=lo, chunk=chunk, causal=True)
+        np.testing.assert_allclose(o, o_full[lo:hi], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse, l_full[:, lo:hi], rtol=0, atol=1e-12)
+    o, lse = oracle.sp_prefill(q_all[:sq], k, v, q_off=0, chunk=chunk, causal=False)
+    o_nc, l_nc = oracle.attention(q_all[:sq], k, v, causal=False)
+    np.testing.assert_allclose(o, o_nc, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(lse, l_nc, rtol=0, atol=1e-12)
+
+
+def test_varlen_is_per_sequence_dense_and_leak_free():
+    lengths = [5, 0, 1, 9, 3]
+    cu = synth.cu_seqlens_of(lengths)
+    t, hq, hkv, d = int(cu[-1]), 4, 2, 8
+    q, k, v = _rand((t, hq, d), 60), _rand((t, hkv, d), 61), _rand((t, hkv, d), 62)
+    o, lse = oracle.varlen(q, k, v, cu)
+    for b, n in enumerate(lengths):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        if n == 0:
+            continue
+        o_b, l_b = brute_force(q[lo:hi], k[lo:hi], v[lo:hi], 0, 0, True, 1 / math.sqrt(d))
+        np.testing.assert_allclose(o[lo:hi], o_b, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse[:, lo:hi], l_b, rtol=0, atol=1e-12)
+    # Q = 0: LSE is ln(position in sequence + 1); any cross-sequence leak changes the count
+    _, lse0 = oracle.varlen(np.zeros_like(q), k, v, cu)
+    pos = np.concatenate([np.arange(n) for n in lengths])
+    assert np.array_equal(np.rint(np.exp(lse0)).astype(int), np.tile(pos + 1, (hq, 1)))
+
+
+def test_input_recipe_statistics():
+    lens = synth.lognormal_lengths(synth.VARLEN_SEED, 20000)
+    assert 650 <= np.median(lens) <= 750
+    assert 0.78 <= (lens < 2048).mean() <= 0.82
+    assert lens.min() >= 1 and lens.max() <= 8192
+    batch = synth.varlen_lengths()
+    assert len(batch) == 257 and batch[-1] == 65536
+    assert synth.visible_pairs(4, 4, 0, 0, True) == 10
+    assert synth.visible_pairs(3, 5, 10, 0, True) == 15
+    assert synth.visible_pairs(3, 5, 0, 10, True) == 0
+    assert synth.visible_pairs(4, 4, 2, 3, True) == sum(
+        1 for i, j in itertools.product(range(4), range(4)) if 3 + j <= 2 + i)
