@@ -1,0 +1,153 @@
+/*
+ * pec_attn -- blockwise causal prefill attention for one GPU's share of a
+ * sequence-parallel (ring) prefill, for AMD MI355X (gfx950).
+ *
+ * C ABI: plain pointers and sizes only.  Unless said otherwise every pointer is a
+ * DEVICE pointer owned by the caller, 16-byte aligned, and every call is
+ * asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default
+ * stream).  The library keeps no state between calls apart from the tuning
+ * options below, allocates no device memory, and never synchronises the device.
+ *
+ * Layouts (row-major, contiguous, counts in elements):
+ *   q, out  : [tokens, n_q_heads, 128]   bf16 (out: bf16 or fp32, see out_dtype)
+ *   k, v    : [tokens, n_kv_heads, 128]  bf16
+ *   lse     : [n_q_heads, tokens]        fp32, natural log of sum_j exp(q.k_j * scale)
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads)  (grouped-query
+ * attention as assumed by the paper's cost model, section "Fast Sequence
+ * Parallelism for Long-Request Prefill").
+ *
+ * Positions: local query row i sits at global position q_off + i, local key j at
+ * kv_off + j.  With causal != 0 key j is visible to row i iff
+ * kv_off + j <= q_off + i  (Eq. 3: the softmax denominator runs up to the row's
+ * own token, which is included).  A row with no visible key gets out = 0 and
+ * lse = -inf; that pair is the identity of pec_attn_merge.
+ *
+ * Every function returns PEC_OK (0) or a negative pec_status; nothing throws or
+ * aborts across this boundary.  Zero-sized problems (sq == 0) are PEC_OK no-ops.
+ */
+#ifndef PEC_ATTN_H
+#define PEC_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PEC_OK = 0,
+    PEC_ERR_INVALID_ARGUMENT = -1, /* null pointer, negative size, n_q_heads % n_kv_heads != 0, scale <= 0 ... */
+    PEC_ERR_UNSUPPORTED = -2,      /* head_dim != 128, unknown dtype / option, size beyond 2^30 rows */
+    PEC_ERR_MISALIGNED = -3,       /* a pointer is not 16-byte aligned */
+    PEC_ERR_WORKSPACE = -4,        /* workspace missing or smaller than pec_*_workspace_bytes() */
+    PEC_ERR_HIP = -5               /* the HIP runtime reported an error at launch */
+} pec_status;
+
+enum { PEC_BF16 = 0, PEC_F32 = 1 };
+
+typedef struct {
+    int32_t n_q_heads;  /* N_h */
+    int32_t n_kv_heads; /* N_h^KV, divides n_q_heads */
+    int32_t head_dim;   /* d_h, must be 128 */
+    int32_t out_dtype;  /* dtype of `out` / `o_acc` / `o_part`: PEC_BF16 (final) or PEC_F32 (partials kept
+                           exact across merges) */
+    float scale;        /* multiplies q.k; 0 selects 1/sqrt(head_dim) (Eq. 2) */
+} pec_shape_t;
+
+/*
+ * One ring step: attention of a local query segment against ONE key/value
+ * segment (Eq. 2 with the softmax of Eq. 3 restricted to that segment's keys),
+ * returned as the partial pair (out, lse).
+ *   q [sq, Hq, 128], k/v [sk, Hkv, 128], out [sq, Hq, 128] (out_dtype), lse [Hq, sq].
+ * sk == 0 or a segment wholly in the future gives out = 0, lse = -inf.
+ */
+int pec_attn_chunk(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                   int64_t sq, int64_t sk, int64_t q_off, int64_t kv_off, int causal,
+                   void* out, float* lse, void* stream);
+
+/*
+ * Same ring step, folded straight into running accumulators: on entry
+ * (o_acc, lse_acc) is the exact result over the keys seen so far, on return it is
+ * the exact result over those keys plus this segment's (the log-sum-exp merge of
+ * pec_attn_merge applied inside the kernel, so the partial never reaches HBM).
+ * o_acc is always fp32 [sq, Hq, 128]; lse_acc [Hq, sq].  If out_final is not NULL
+ * the merged result is ALSO written there in shape->out_dtype (used for the last
+ * ring step); o_acc/lse_acc are updated in either case.
+ */
+int pec_attn_chunk_merge(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                         int64_t sq, int64_t sk, int64_t q_off, int64_t kv_off, int causal,
+                         float* o_acc, float* lse_acc, void* out_final, void* stream);
+
+/*
+ * Exact merge of two partial results over disjoint key sets (the online-softmax
+ * step of ring attention, section "Sequence Parallelism for Long Requests"):
+ *   L = ln(exp(lse_acc) + exp(lse_part)),
+ *   o_acc = o_acc * exp(lse_acc - L) + o_part * exp(lse_part - L),  lse_acc = L.
+ * In place on (o_acc, lse_acc).  o_acc and o_part are [sq, Hq, 128] in
+ * shape->out_dtype, the lse arrays [Hq, sq] fp32.  (0, -inf) is the identity.
+ */
+int pec_attn_merge(const pec_shape_t* shape, void* o_acc, float* lse_acc,
+                   const void* o_part, const float* lse_part, int64_t sq, void* stream);
+
+/* fp32 [sq, Hq, 128] -> bf16, round to nearest even.  For callers that merged fp32 partials. */
+int pec_finalize(const pec_shape_t* shape, const float* o_f32, void* o_bf16, int64_t sq, void* stream);
+
+/*
+ * One ring member's whole prefill on one GPU: the query segment q [s_q, Hq, 128]
+ * at global offset q_off attends over k/v [s_kv, Hkv, 128] (global positions
+ * 0..s_kv-1) cut into contiguous segments of `chunk` tokens (the last may be
+ * short).  Segments are visited in ring order starting from the member's own,
+ * (r - t) mod P for step t with r = q_off / chunk; under the causal mask segments
+ * wholly in the future are skipped.  Each step is a separate kernel launch, so a
+ * scheduler can stop between two steps (section "Preemption of Long-Request
+ * Prefill").  How the partials are combined is chosen by PEC_OPT_SP_MODE.
+ *   out [s_q, Hq, 128] in shape->out_dtype, lse [Hq, s_q].
+ * workspace: device scratch of at least pec_sp_workspace_bytes() bytes, 16-byte
+ * aligned; contents undefined on return.
+ */
+int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                   int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk, int causal,
+                   void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
+
+/*
+ * Packed batch of independent prompts (batched short prefills colocated with a
+ * long request, section "Coordinated Prefill-Decode Colocation and
+ * Disaggregation"): sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1 of
+ * q/k/v/out, attends only to itself, positions restart at 0.
+ *   cu_seqlens: DEVICE int32 [batch + 1], non-decreasing, cu_seqlens[0] == 0,
+ *               cu_seqlens[batch] == total_tokens (not checked; otherwise undefined).
+ *   max_seqlen: upper bound on any sequence length (host value).
+ *   lse [Hq, total_tokens].  Zero-length sequences are legal.
+ * workspace: at least pec_varlen_workspace_bytes() bytes (the device-built work list).
+ */
+int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                    const int32_t* cu_seqlens, int32_t batch, int64_t total_tokens, int32_t max_seqlen,
+                    int causal, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens);
+
+/* Tuning knobs; process-wide, not thread-safe against concurrent calls. */
+enum {
+    PEC_OPT_KERNEL_VARIANT = 0, /* see PEC_VARIANT_* */
+    PEC_OPT_SP_MODE = 1         /* see PEC_SP_* */
+};
+enum {
+    PEC_VARIANT_W4_Q64 = 0,      /* 4 wavefronts x 64 query rows, transposing LDS reads for V (default) */
+    PEC_VARIANT_W8_Q32 = 1,      /* 8 wavefronts x 32 query rows */
+    PEC_VARIANT_W4_Q64_NOTR = 2  /* as 0 but V operands gathered with scalar LDS reads (slow; cross-check) */
+};
+enum {
+    PEC_SP_FUSED_MERGE = 0,   /* one pec_attn_chunk_merge launch per ring step (default) */
+    PEC_SP_SEPARATE_MERGE = 1,/* pec_attn_chunk -> fp32 partial -> pec_attn_merge per ring step */
+    PEC_SP_SINGLE_LAUNCH = 2  /* one launch sweeping all segments with the running state in registers */
+};
+int pec_set_option(int option, int value);
+int pec_get_option(int option);
+
+const char* pec_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PEC_ATTN_H */

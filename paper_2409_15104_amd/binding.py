@@ -1,0 +1,222 @@
+"""ctypes binding of libpec_attn.so: argument marshalling only.
+
+Function names and argument order follow include/pec_attn.h.  torch supplies
+device memory and the current HIP stream; every step of the computation runs in
+the library's kernels.  There is no fallback: a missing library or a non-zero
+status raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpec_attn.so")
+
+PEC_BF16, PEC_F32 = 0, 1
+PEC_OPT_KERNEL_VARIANT, PEC_OPT_SP_MODE = 0, 1
+PEC_VARIANT_W4_Q64, PEC_VARIANT_W8_Q32, PEC_VARIANT_W4_Q64_NOTR = 0, 1, 2
+PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
+
+EXPORTS = (
+    "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
+    "pec_sp_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
+    "pec_get_option", "pec_status_string",
+)
+
+
+class PecShape(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class PecError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (fn, status_string(status), status))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libpec_attn.so is missing: run `python -m paper_2409_15104_amd.build` (hipcc, gfx950) first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_size_t
+        sp = ctypes.POINTER(PecShape)
+        L.pec_attn_chunk.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp]
+        L.pec_attn_chunk_merge.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp, vp]
+        L.pec_attn_merge.argtypes = [sp, vp, vp, vp, vp, i64, vp]
+        L.pec_finalize.argtypes = [sp, vp, vp, i64, vp]
+        L.pec_sp_prefill.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp, sz, vp]
+        L.pec_sp_workspace_bytes.argtypes = [sp, i64]
+        L.pec_sp_workspace_bytes.restype = sz
+        L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
+        L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
+        L.pec_varlen_workspace_bytes.restype = sz
+        L.pec_set_option.argtypes = [ci, ci]
+        L.pec_get_option.argtypes = [ci]
+        L.pec_status_string.argtypes = [ci]
+        L.pec_status_string.restype = ctypes.c_char_p
+        for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
+                     "pec_attn_varlen", "pec_set_option", "pec_get_option"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().pec_status_string(int(status)).decode()
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise PecError(fn, status)
+
+
+def _shape(q: torch.Tensor, k: torch.Tensor, out_dtype, scale: float) -> PecShape:
+    return PecShape(q.shape[1], k.shape[1], q.shape[2], PEC_F32 if out_dtype == torch.float32 else PEC_BF16,
+                    float(scale))
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _require(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise ValueError("%s must be a contiguous %s tensor on the GPU" % (name, dtype))
+
+
+def pec_set_option(option: int, value: int) -> None:
+    _check("pec_set_option", lib().pec_set_option(int(option), int(value)))
+
+
+def pec_get_option(option: int) -> int:
+    return int(lib().pec_get_option(int(option)))
+
+
+def pec_attn_chunk(q, k, v, q_off: int, kv_off: int, causal: bool = True, out_dtype=torch.bfloat16,
+                   scale: float = 0.0, out=None, lse=None, stream=None):
+    """q [sq,Hq,128], k/v [sk,Hkv,128] bf16 -> (out [sq,Hq,128] out_dtype, lse [Hq,sq] fp32)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    sq, hq, d = q.shape
+    sk = k.shape[0]
+    if out is None:
+        out = torch.empty((sq, hq, d), dtype=out_dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((hq, sq), dtype=torch.float32, device=q.device)
+    _require(out, out_dtype, "out")
+    _require(lse, torch.float32, "lse")
+    shp = _shape(q, k, out_dtype, scale)
+    _check("pec_attn_chunk", lib().pec_attn_chunk(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), sq, sk, int(q_off),
+                                                  int(kv_off), int(bool(causal)), _ptr(out), _ptr(lse),
+                                                  _stream(stream)))
+    return out, lse
+
+
+def pec_attn_chunk_merge(q, k, v, q_off: int, kv_off: int, o_acc, lse_acc, causal: bool = True, out_final=None,
+                         scale: float = 0.0, stream=None):
+    """Fold one KV segment into the running fp32 (o_acc, lse_acc) in place; optionally also emit out_final."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    _require(o_acc, torch.float32, "o_acc")
+    _require(lse_acc, torch.float32, "lse_acc")
+    out_dtype = out_final.dtype if out_final is not None else torch.bfloat16
+    shp = _shape(q, k, out_dtype, scale)
+    _check("pec_attn_chunk_merge",
+           lib().pec_attn_chunk_merge(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), q.shape[0], k.shape[0], int(q_off),
+                                      int(kv_off), int(bool(causal)), _ptr(o_acc), _ptr(lse_acc), _ptr(out_final),
+                                      _stream(stream)))
+    return o_acc, lse_acc
+
+
+def pec_attn_merge(o_acc, lse_acc, o_part, lse_part, stream=None):
+    """In-place exact merge of (o_part, lse_part) into (o_acc, lse_acc); o_* share a dtype (bf16 or fp32)."""
+    if o_acc.dtype != o_part.dtype:
+        raise ValueError("o_acc and o_part must share a dtype")
+    _require(o_acc, o_acc.dtype, "o_acc")
+    _require(o_part, o_acc.dtype, "o_part")
+    _require(lse_acc, torch.float32, "lse_acc")
+    _require(lse_part, torch.float32, "lse_part")
+    sq, hq, d = o_acc.shape
+    shp = PecShape(hq, hq, d, PEC_F32 if o_acc.dtype == torch.float32 else PEC_BF16, 0.0)
+    _check("pec_attn_merge", lib().pec_attn_merge(ctypes.byref(shp), _ptr(o_acc), _ptr(lse_acc), _ptr(o_part),
+                                                  _ptr(lse_part), sq, _stream(stream)))
+    return o_acc, lse_acc
+
+
+def pec_finalize(o_f32, o_bf16=None, stream=None):
+    _require(o_f32, torch.float32, "o_f32")
+    sq, hq, d = o_f32.shape
+    if o_bf16 is None:
+        o_bf16 = torch.empty((sq, hq, d), dtype=torch.bfloat16, device=o_f32.device)
+    shp = PecShape(hq, hq, d, PEC_BF16, 0.0)
+    _check("pec_finalize", lib().pec_finalize(ctypes.byref(shp), _ptr(o_f32), _ptr(o_bf16), sq, _stream(stream)))
+    return o_bf16
+
+
+def pec_sp_workspace_bytes(n_q_heads: int, n_kv_heads: int, s_q: int) -> int:
+    shp = PecShape(n_q_heads, n_kv_heads, 128, PEC_BF16, 0.0)
+    return int(lib().pec_sp_workspace_bytes(ctypes.byref(shp), int(s_q)))
+
+
+def pec_sp_prefill(q, k, v, q_off: int, chunk: int, causal: bool = True, out_dtype=torch.bfloat16,
+                   scale: float = 0.0, out=None, lse=None, workspace=None, stream=None):
+    """One ring member's prefill: q [s_q,Hq,128] at q_off vs k/v [s_kv,Hkv,128] in segments of `chunk`."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    s_q, hq, d = q.shape
+    s_kv = k.shape[0]
+    if out is None:
+        out = torch.empty((s_q, hq, d), dtype=out_dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((hq, s_q), dtype=torch.float32, device=q.device)
+    shp = _shape(q, k, out_dtype, scale)
+    if workspace is None:
+        workspace = torch.empty(max(16, int(lib().pec_sp_workspace_bytes(ctypes.byref(shp), s_q))), dtype=torch.uint8,
+                                device=q.device)
+    _check("pec_sp_prefill",
+           lib().pec_sp_prefill(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), s_q, int(q_off), s_kv, int(chunk),
+                                int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(),
+                                _stream(stream)))
+    return out, lse
+
+
+def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:
+    return int(lib().pec_varlen_workspace_bytes(int(batch), int(total_tokens)))
+
+
+def pec_attn_varlen(q, k, v, cu_seqlens, max_seqlen: int, causal: bool = True, out_dtype=torch.bfloat16,
+                    scale: float = 0.0, out=None, lse=None, workspace=None, stream=None):
+    """Packed batch: q [T,Hq,128], k/v [T,Hkv,128], cu_seqlens int32 [B+1] on the GPU."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    _require(cu_seqlens, torch.int32, "cu_seqlens")
+    total, hq, d = q.shape
+    batch = cu_seqlens.numel() - 1
+    if out is None:
+        out = torch.empty((total, hq, d), dtype=out_dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((hq, total), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, pec_varlen_workspace_bytes(batch, total)), dtype=torch.uint8, device=q.device)
+    shp = _shape(q, k, out_dtype, scale)
+    _check("pec_attn_varlen",
+           lib().pec_attn_varlen(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), batch, total,
+                                 int(max_seqlen), int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace),
+                                 workspace.numel(), _stream(stream)))
+    return out, lse

@@ -1,0 +1,106 @@
+// HBM-bound helpers around the attention kernel: the log-sum-exp merge of two
+// partial results, the fp32 -> bf16 finalisation, and the device-side work list for
+// packed variable-length batches.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fwd_kernel.hpp"
+
+namespace pec {
+
+// o_acc <- o_acc * exp(la - L) + o_part * exp(lb - L),  L = ln(exp(la) + exp(lb)).
+// One thread per 4 consecutive head-dim values; the 32 threads of one (row, head)
+// sit in one wavefront, so all of them read lse_acc before thread 0 overwrites it.
+template <bool F32>
+__global__ __launch_bounds__(256) void merge_kernel(void* __restrict__ o_acc_v, float* __restrict__ lse_acc,
+                                                    const void* __restrict__ o_part_v,
+                                                    const float* __restrict__ lse_part, int64_t sq, int n_q_heads) {
+    const int64_t n_groups = sq * n_q_heads * 32;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n_groups;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t rh = g >> 5;
+        const int64_t row = rh / n_q_heads;
+        const int h = (int)(rh % n_q_heads);
+        const int64_t li = (int64_t)h * sq + row;
+        const float la = lse_acc[li], lb = lse_part[li];
+        const float mx = fmaxf(la, lb);
+        float wa = 0.f, wb = 0.f, L = -INFINITY;
+        if (mx != -INFINITY) {
+            const float ea = expf(la - mx), eb = expf(lb - mx);
+            const float den = ea + eb;
+            wa = ea / den;
+            wb = eb / den;
+            L = mx + logf(den);
+        }
+        f32x4 a, b;
+        if constexpr (F32) {
+            a = reinterpret_cast<const f32x4*>(o_acc_v)[g];
+            b = reinterpret_cast<const f32x4*>(o_part_v)[g];
+        } else {
+            a = __builtin_convertvector(reinterpret_cast<const bf16x4*>(o_acc_v)[g], f32x4);
+            b = __builtin_convertvector(reinterpret_cast<const bf16x4*>(o_part_v)[g], f32x4);
+        }
+        f32x4 r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = a[i] * wa + b[i] * wb;
+        if constexpr (F32)
+            reinterpret_cast<f32x4*>(o_acc_v)[g] = r;
+        else
+            reinterpret_cast<bf16x4*>(o_acc_v)[g] = __builtin_convertvector(r, bf16x4);
+        if ((g & 31) == 0) lse_acc[li] = L;
+    }
+}
+
+__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ src, __bf16* __restrict__ dst,
+                                                       int64_t n_groups) {
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n_groups;
+         g += (int64_t)gridDim.x * blockDim.x)
+        reinterpret_cast<bf16x4*>(dst)[g] = __builtin_convertvector(reinterpret_cast<const f32x4*>(src)[g], bf16x4);
+}
+
+// Work list for a packed batch: one item per (sequence, query tile), ordered by
+// descending query-tile index so the longest causal rows start first.  Single
+// workgroup; `bucket` and `cursor` are int32[max_qtiles] scratch.
+__global__ __launch_bounds__(1024) void build_worklist_kernel(const int32_t* __restrict__ cu, int batch, int bm,
+                                                              int max_qtiles, int capacity,
+                                                              WorkItem* __restrict__ work,
+                                                              int32_t* __restrict__ n_work,
+                                                              int32_t* __restrict__ bucket,
+                                                              int32_t* __restrict__ cursor) {
+    const int tid = threadIdx.x;
+    for (int t = tid; t < max_qtiles; t += blockDim.x) {
+        bucket[t] = 0;
+        cursor[t] = 0;
+    }
+    __syncthreads();
+    for (int b = tid; b < batch; b += blockDim.x) {
+        const int len = cu[b + 1] - cu[b];
+        const int nq = min(max_qtiles, (len + bm - 1) / bm);
+        for (int t = 0; t < nq; ++t) atomicAdd(&bucket[t], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;   // bucket[t] becomes the list position of the first item with tile index t
+        for (int t = max_qtiles - 1; t >= 0; --t) {
+            const int c = bucket[t];
+            bucket[t] = run;
+            run += c;
+        }
+        *n_work = min(run, capacity);
+    }
+    __syncthreads();
+    for (int b = tid; b < batch; b += blockDim.x) {
+        const int len = cu[b + 1] - cu[b];
+        const int nq = min(max_qtiles, (len + bm - 1) / bm);
+        for (int t = 0; t < nq; ++t) {
+            const int pos = bucket[t] + atomicAdd(&cursor[t], 1);
+            if (pos < capacity) {   // only a malformed cu_seqlens can overflow the list
+                work[pos].seq = b;
+                work[pos].qtile = t;
+            }
+        }
+    }
+}
+
+}  // namespace pec

@@ -1,0 +1,355 @@
+// C-ABI host side of pec_attn: argument validation, launch geometry, ring-order
+// chunk schedule.  All arithmetic of the method runs in the kernels.
+#include "../../include/pec_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+
+#include "aux_kernels.hpp"
+#include "fwd_kernel.hpp"
+
+namespace {
+
+using namespace pec;
+
+enum { VARIANT_W4_Q64 = 0, VARIANT_W8_Q32 = 1, VARIANT_W4_Q64_NOTR = 2, N_VARIANTS = 3 };
+
+int g_variant = VARIANT_W4_Q64;
+int g_sp_mode = PEC_SP_FUSED_MERGE;
+
+constexpr int64_t kMaxRows = (int64_t)1 << 30;
+constexpr int kBM = 256;           // query rows per workgroup, the same for every variant
+constexpr int kMinBM = 128;        // used only to bound work-list sizes
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_shape(const pec_shape_t* s, float* scale_out) {
+    if (!s) return PEC_ERR_INVALID_ARGUMENT;
+    if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (s->head_dim != kHeadDim) return PEC_ERR_UNSUPPORTED;
+    if (s->out_dtype != PEC_BF16 && s->out_dtype != PEC_F32) return PEC_ERR_UNSUPPORTED;
+    float scale = s->scale;
+    if (scale == 0.f) scale = 1.0f / std::sqrt((float)s->head_dim);
+    if (!(scale > 0.f) || !std::isfinite(scale)) return PEC_ERR_INVALID_ARGUMENT;
+    if (scale_out) *scale_out = scale;
+    return PEC_OK;
+}
+
+int launch_fwd(const FwdParams& p, hipStream_t stream) {
+    const int64_t total = (int64_t)p.n_items * p.n_q_heads;
+    if (total <= 0) return PEC_OK;
+    const int64_t per_xcd = (total + 7) / 8;
+    const int64_t grid = per_xcd * 8;
+    if (grid > 0x7fffffffLL) return PEC_ERR_UNSUPPORTED;
+    switch (g_variant) {
+        case VARIANT_W4_Q64:
+            hipLaunchKernelGGL((fwd_kernel<2, 4, true>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+            break;
+        case VARIANT_W8_Q32:
+            hipLaunchKernelGGL((fwd_kernel<1, 8, true>), dim3((unsigned)grid), dim3(512), 0, stream, p);
+            break;
+        default:
+            hipLaunchKernelGGL((fwd_kernel<2, 4, false>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+            break;
+    }
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
+// Common body of pec_attn_chunk / pec_attn_chunk_merge.
+int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sq, int64_t sk,
+               int64_t q_off, int64_t kv_off, int causal, void* out, int out_f32, float* lse, const float* acc_in,
+               const float* lse_in, float* acc_out, int64_t lse_stride, void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (sq < 0 || sk < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (sq > kMaxRows || sk > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (sq == 0) return PEC_OK;
+    if (!q || !lse || (!out && !acc_out) || (sk > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(acc_in) ||
+        misaligned(acc_out) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return PEC_ERR_MISALIGNED;
+
+    FwdParams p{};
+    p.q = static_cast<const __bf16*>(q);
+    p.k = static_cast<const __bf16*>(k);
+    p.v = static_cast<const __bf16*>(v);
+    p.out = out;
+    p.lse = lse;
+    p.acc_in = acc_in;
+    p.lse_in = lse_in;
+    p.acc_out = acc_out;
+    p.lse_stride = lse_stride;
+    p.sq = (int32_t)sq;
+    p.sk = (int32_t)sk;
+    // key j visible to row i  <=>  j <= i + (q_off - kv_off); beyond [-sq-1, sk] the value no longer matters
+    const int64_t d = q_off - kv_off;
+    p.delta = (int32_t)std::max<int64_t>(-sq - 1, std::min<int64_t>(d, sk));
+    p.causal = causal ? 1 : 0;
+    p.n_q_heads = shape->n_q_heads;
+    p.n_kv_heads = shape->n_kv_heads;
+    p.group = shape->n_q_heads / shape->n_kv_heads;
+    p.n_items = (int32_t)((sq + kBM - 1) / kBM);
+    p.out_f32 = out_f32;
+    p.scale_log2 = scale * kLog2e;
+    return launch_fwd(p, static_cast<hipStream_t>(stream));
+}
+
+int grid_for(int64_t n_groups) { return (int)std::min<int64_t>((n_groups + 255) / 256, 256 * 32); }
+
+}  // namespace
+
+extern "C" {
+
+int pec_attn_chunk(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sq, int64_t sk,
+                   int64_t q_off, int64_t kv_off, int causal, void* out, float* lse, void* stream) {
+    if (sq > 0 && !out) return PEC_ERR_INVALID_ARGUMENT;
+    return chunk_impl(shape, q, k, v, sq, sk, q_off, kv_off, causal, out, shape ? shape->out_dtype == PEC_F32 : 0, lse,
+                      nullptr, nullptr, nullptr, sq, stream);
+}
+
+int pec_attn_chunk_merge(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sq, int64_t sk,
+                         int64_t q_off, int64_t kv_off, int causal, float* o_acc, float* lse_acc, void* out_final,
+                         void* stream) {
+    if (sq > 0 && (!o_acc || !lse_acc)) return PEC_ERR_INVALID_ARGUMENT;
+    return chunk_impl(shape, q, k, v, sq, sk, q_off, kv_off, causal, out_final,
+                      shape ? shape->out_dtype == PEC_F32 : 0, lse_acc, o_acc, lse_acc, o_acc, sq, stream);
+}
+
+int pec_attn_merge(const pec_shape_t* shape, void* o_acc, float* lse_acc, const void* o_part, const float* lse_part,
+                   int64_t sq, void* stream) {
+    if (int rc = check_shape(shape, nullptr)) return rc;
+    if (sq < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (sq > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (sq == 0) return PEC_OK;
+    if (!o_acc || !lse_acc || !o_part || !lse_part) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(o_acc) || misaligned(o_part)) return PEC_ERR_MISALIGNED;
+    const int64_t n_groups = sq * shape->n_q_heads * 32;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (shape->out_dtype == PEC_F32)
+        hipLaunchKernelGGL((merge_kernel<true>), dim3(grid_for(n_groups)), dim3(256), 0, st, o_acc, lse_acc, o_part,
+                           lse_part, sq, shape->n_q_heads);
+    else
+        hipLaunchKernelGGL((merge_kernel<false>), dim3(grid_for(n_groups)), dim3(256), 0, st, o_acc, lse_acc, o_part,
+                           lse_part, sq, shape->n_q_heads);
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
+int pec_finalize(const pec_shape_t* shape, const float* o_f32, void* o_bf16, int64_t sq, void* stream) {
+    if (int rc = check_shape(shape, nullptr)) return rc;
+    if (sq < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (sq > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (sq == 0) return PEC_OK;
+    if (!o_f32 || !o_bf16) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(o_f32) || misaligned(o_bf16)) return PEC_ERR_MISALIGNED;
+    const int64_t n_groups = sq * shape->n_q_heads * 32;
+    hipLaunchKernelGGL(finalize_kernel, dim3(grid_for(n_groups)), dim3(256), 0, static_cast<hipStream_t>(stream), o_f32,
+                       static_cast<__bf16*>(o_bf16), n_groups);
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
+size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q) {
+    if (!shape || s_q <= 0 || shape->n_q_heads <= 0) return 0;
+    // running fp32 O, one fp32 partial O, one partial LSE (the last two only in PEC_SP_SEPARATE_MERGE)
+    const size_t o = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
+    const size_t l = (((size_t)s_q * shape->n_q_heads * sizeof(float)) + 255) & ~(size_t)255;
+    return 2 * o + l;
+}
+
+int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t s_q, int64_t q_off,
+                   int64_t s_kv, int64_t chunk, int causal, void* out, float* lse, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (s_q < 0 || s_kv < 0 || chunk <= 0 || q_off < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (s_q > kMaxRows || s_kv > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (s_q == 0) return PEC_OK;
+    if (!q || !out || !lse || (s_kv > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(out) || misaligned(workspace)) return PEC_ERR_MISALIGNED;
+    const int out_f32 = shape->out_dtype == PEC_F32;
+    const int64_t kv_row = (int64_t)shape->n_kv_heads * kHeadDim;  // elements per token
+    const __bf16* kp = static_cast<const __bf16*>(k);
+    const __bf16* vp = static_cast<const __bf16*>(v);
+
+    if (g_sp_mode == PEC_SP_SINGLE_LAUNCH || s_kv == 0)
+        return chunk_impl(shape, q, k, v, s_q, s_kv, q_off, 0, causal, out, out_f32, lse, nullptr, nullptr, nullptr, s_q,
+                          stream);
+
+    // ring order: step t brings segment (r - t) mod P, the member's own segment first
+    const int64_t n_chunks = (s_kv + chunk - 1) / chunk;
+    const int64_t r = std::min(q_off / chunk, n_chunks - 1);
+    int64_t visit_count = 0;
+    for (int64_t t = 0; t < n_chunks; ++t) {
+        const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
+        if (causal && c * chunk > q_off + s_q - 1) continue;
+        ++visit_count;
+    }
+    if (visit_count == 0)  // nothing visible at all: out = 0, lse = -inf
+        return chunk_impl(shape, q, k, v, s_q, 0, q_off, 0, causal, out, out_f32, lse, nullptr, nullptr, nullptr, s_q,
+                          stream);
+    if (visit_count == 1) {
+        for (int64_t t = 0; t < n_chunks; ++t) {
+            const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
+            if (causal && c * chunk > q_off + s_q - 1) continue;
+            const int64_t lo = c * chunk, len = std::min(chunk, s_kv - lo);
+            return chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, out, out_f32,
+                              lse, nullptr, nullptr, nullptr, s_q, stream);
+        }
+    }
+
+    if (!workspace || workspace_bytes < pec_sp_workspace_bytes(shape, s_q)) return PEC_ERR_WORKSPACE;
+    const size_t o_bytes = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
+    float* o_acc = static_cast<float*>(workspace);
+    float* o_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + o_bytes);
+    float* lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * o_bytes);
+    pec_shape_t part_shape = *shape;
+    part_shape.out_dtype = PEC_F32;
+
+    int64_t visited = 0;
+    for (int64_t t = 0; t < n_chunks; ++t) {
+        const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
+        const int64_t lo = c * chunk, len = std::min(chunk, s_kv - lo);
+        if (causal && lo > q_off + s_q - 1) continue;  // wholly in the future of every local query
+        const bool first = visited == 0, last = visited == visit_count - 1;
+        int rc;
+        if (g_sp_mode == PEC_SP_FUSED_MERGE) {
+            if (first)  // starts the running state: plain chunk call writing fp32 O into o_acc
+                rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_acc,
+                                1, lse, nullptr, nullptr, nullptr, s_q, stream);
+            else if (!last)
+                rc = chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, nullptr,
+                                out_f32, lse, o_acc, lse, o_acc, s_q, stream);
+            else  // last step: the merged result goes straight to `out`
+                rc = chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, out, out_f32,
+                                lse, o_acc, lse, nullptr, s_q, stream);
+        } else {
+            if (first) {
+                rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_acc,
+                                1, lse, nullptr, nullptr, nullptr, s_q, stream);
+            } else {
+                rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_part,
+                                1, lse_part, nullptr, nullptr, nullptr, s_q, stream);
+                if (rc == PEC_OK) rc = pec_attn_merge(&part_shape, o_acc, lse, o_part, lse_part, s_q, stream);
+            }
+            if (rc == PEC_OK && last) {
+                if (out_f32) {
+                    if (hipMemcpyAsync(out, o_acc, o_bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)) !=
+                        hipSuccess)
+                        rc = PEC_ERR_HIP;
+                } else {
+                    rc = pec_finalize(shape, o_acc, out, s_q, stream);
+                }
+            }
+        }
+        if (rc != PEC_OK) return rc;
+        ++visited;
+    }
+    return PEC_OK;
+}
+
+size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens) {
+    if (batch < 0 || total_tokens < 0) return 0;
+    const size_t cap = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;
+    // work list + counter (padded) + two int32 arrays indexed by query-tile number
+    return cap * sizeof(WorkItem) + 256 + 2 * cap * sizeof(int32_t);
+}
+
+int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                    int32_t batch, int64_t total_tokens, int32_t max_seqlen, int causal, void* out, float* lse,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (batch < 0 || total_tokens < 0 || max_seqlen < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (total_tokens > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (batch == 0 || total_tokens == 0 || max_seqlen == 0) return PEC_OK;
+    if (!q || !k || !v || !out || !lse || !cu_seqlens) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace) ||
+        (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u))
+        return PEC_ERR_MISALIGNED;
+    if (!workspace || workspace_bytes < pec_varlen_workspace_bytes(batch, total_tokens)) return PEC_ERR_WORKSPACE;
+
+    const int64_t max_len = std::min<int64_t>(max_seqlen, total_tokens);
+    const int max_qtiles = (int)((max_len + kBM - 1) / kBM);
+    // every sequence contributes at most len/BM + 1 items
+    const int64_t cap64 = total_tokens / kBM + batch;
+    const size_t cap_alloc = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;
+    const int capacity = (int)std::min<int64_t>(cap64, (int64_t)cap_alloc);
+    char* ws = static_cast<char*>(workspace);
+    WorkItem* work = reinterpret_cast<WorkItem*>(ws);
+    int32_t* n_work = reinterpret_cast<int32_t*>(ws + cap_alloc * sizeof(WorkItem));
+    int32_t* bucket = reinterpret_cast<int32_t*>(ws + cap_alloc * sizeof(WorkItem) + 256);
+    int32_t* cursor = bucket + cap_alloc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(build_worklist_kernel, dim3(1), dim3(1024), 0, st, cu_seqlens, (int)batch, kBM, max_qtiles,
+                       capacity, work, n_work, bucket, cursor);
+    if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+
+    FwdParams p{};
+    p.q = static_cast<const __bf16*>(q);
+    p.k = static_cast<const __bf16*>(k);
+    p.v = static_cast<const __bf16*>(v);
+    p.out = out;
+    p.lse = lse;
+    p.lse_stride = total_tokens;
+    p.causal = causal ? 1 : 0;
+    p.n_q_heads = shape->n_q_heads;
+    p.n_kv_heads = shape->n_kv_heads;
+    p.group = shape->n_q_heads / shape->n_kv_heads;
+    p.n_items = capacity;
+    p.out_f32 = shape->out_dtype == PEC_F32;
+    p.scale_log2 = scale * kLog2e;
+    p.cu_seqlens = cu_seqlens;
+    p.work = work;
+    p.n_work = n_work;
+    p.total_tokens = (int32_t)total_tokens;
+    return launch_fwd(p, st);
+}
+
+int pec_set_option(int option, int value) {
+    switch (option) {
+        case PEC_OPT_KERNEL_VARIANT:
+            if (value < 0 || value >= N_VARIANTS) return PEC_ERR_UNSUPPORTED;
+            g_variant = value;
+            return PEC_OK;
+        case PEC_OPT_SP_MODE:
+            if (value < PEC_SP_FUSED_MERGE || value > PEC_SP_SINGLE_LAUNCH) return PEC_ERR_UNSUPPORTED;
+            g_sp_mode = value;
+            return PEC_OK;
+        default:
+            return PEC_ERR_UNSUPPORTED;
+    }
+}
+
+int pec_get_option(int option) {
+    switch (option) {
+        case PEC_OPT_KERNEL_VARIANT:
+            return g_variant;
+        case PEC_OPT_SP_MODE:
+            return g_sp_mode;
+        default:
+            return PEC_ERR_UNSUPPORTED;
+    }
+}
+
+const char* pec_status_string(int status) {
+    switch (status) {
+        case PEC_OK:
+            return "ok";
+        case PEC_ERR_INVALID_ARGUMENT:
+            return "invalid argument";
+        case PEC_ERR_UNSUPPORTED:
+            return "unsupported configuration";
+        case PEC_ERR_MISALIGNED:
+            return "pointer not 16-byte aligned";
+        case PEC_ERR_WORKSPACE:
+            return "workspace missing or too small";
+        case PEC_ERR_HIP:
+            return "HIP runtime error";
+        default:
+            return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,288 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle.
+
+Tolerances (from the task definition): max-abs 2e-2 on bf16 outputs,
+|dLSE| <= 1e-3 * max(1, |LSE|) on fp32 LSE, -inf exactly where no key is visible;
+mask / offset / cu_seqlens indexing is checked bit-exactly through closed forms.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as oracle
+from paper_2409_15104_amd import binding as pec
+from paper_2409_15104_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+O_ATOL = 2e-2
+LSE_RTOL = 1e-3
+DEV = "cuda:0"
+VARIANTS = [pec.PEC_VARIANT_W4_Q64, pec.PEC_VARIANT_W8_Q32, pec.PEC_VARIANT_W4_Q64_NOTR]
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, pec.PEC_VARIANT_W4_Q64)
+    pec.pec_set_option(pec.PEC_OPT_SP_MODE, pec.PEC_SP_FUSED_MERGE)
+    yield
+    torch.cuda.synchronize()
+
+
+def assert_close(out, lse, o_ref, l_ref, what=""):
+    o = out.float().cpu().numpy().astype(np.float64)
+    l = lse.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(o).any() and not np.isnan(l).any(), what
+    err = np.abs(o - o_ref).max() if o.size else 0.0
+    assert err <= O_ATOL, "%s: max-abs O error %.4g" % (what, err)
+    fin = np.isfinite(l_ref)
+    assert np.array_equal(np.isfinite(l), fin), what + ": -inf pattern of LSE differs"
+    assert np.all(l[~fin] == -np.inf)
+    if fin.any():
+        rel = (np.abs(l[fin] - l_ref[fin]) / np.maximum(1.0, np.abs(l_ref[fin]))).max()
+        assert rel <= LSE_RTOL, "%s: LSE error %.4g" % (what, rel)
+    # rows without a visible key are exactly zero
+    assert np.all(o[np.transpose(~fin)] == 0.0), what
+
+
+def gpu(*ts):
+    return [t.to(DEV) for t in ts]
+
+
+CHUNK_CASES = [
+    # sq, sk, hq, hkv, q_off, kv_off, causal
+    (300, 333, 4, 2, 33, 0, True),      # ragged both ways, several tiles, all rows see something
+    (257, 130, 2, 1, 0, 0, True),       # one row into the second query tile
+    (64, 64, 2, 2, 0, 0, True),         # exactly one tile
+    (520, 200, 4, 1, 0, 100, True),     # first 100 rows see nothing of this segment
+    (96, 128, 2, 2, 0, 1000, True),     # segment wholly in the future
+    (200, 450, 8, 2, 5000, 0, True),    # segment wholly in the past: no masking
+    (130, 77, 4, 4, 0, 0, False),       # non-causal
+    (1, 1, 2, 1, 0, 0, True),
+    (1, 700, 8, 8, 699, 0, True),       # a decode-like single row
+    (40, 0, 2, 2, 0, 0, True),          # no keys at all
+]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("case", CHUNK_CASES)
+def test_chunk_matches_oracle(case, variant):
+    sq, sk, hq, hkv, q_off, kv_off, causal = case
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
+    q, k, v = synth.qkv(7 + sq + sk, sq, sk, hq, hkv)
+    o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=kv_off, causal=causal)
+    for out_dtype in (torch.bfloat16, torch.float32):
+        out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, kv_off, causal, out_dtype=out_dtype)
+        assert_close(out, lse, o_ref, l_ref, "chunk %s v%d %s" % (case, variant, out_dtype))
+
+
+def test_chunk_empty_query_is_a_noop():
+    q, k, v = synth.qkv(3, 0, 16, 2, 2)
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), 0, 0)
+    assert out.shape == (0, 2, 128) and lse.shape == (2, 0)
+
+
+@pytest.mark.parametrize("variant", VARIANTS[:2])
+@pytest.mark.parametrize("q_off,kv_off,sq,sk", [(0, 0, 600, 600), (1000, 937, 333, 700), (5, 200, 300, 90),
+                                               (0, 64, 256, 256), (255, 0, 258, 515)])
+def test_mask_is_bit_exact_via_zero_query(q_off, kv_off, sq, sk, variant):
+    """Q = 0 gives LSE_i = ln n_i with n_i the visible-key count; a one-hot V column gives
+    exactly 1/n_i or exactly 0: any off-by-one in mask or offsets shows."""
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
+    hq, hkv = 4, 2
+    _, k, _ = synth.qkv(11, sq, sk, hq, hkv)
+    q = torch.zeros(sq, hq, 128, dtype=torch.bfloat16)
+    jstar = sk // 2
+    v = torch.zeros(sk, hkv, 128, dtype=torch.bfloat16)
+    v[jstar] = 1.0
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, kv_off, True, out_dtype=torch.float32)
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    n = np.clip(q_off + np.arange(sq) - kv_off + 1, 0, sk)
+    vis = n > 0
+    assert np.all(lse[:, ~vis] == -np.inf)
+    assert np.array_equal(np.rint(np.exp(lse[:, vis].astype(np.float64))).astype(np.int64),
+                          np.tile(n[vis], (hq, 1)))
+    sees = n > jstar
+    assert np.all(out[~sees] == 0.0)
+    np.testing.assert_allclose(out[sees], np.broadcast_to((1.0 / n[sees])[:, None, None], out[sees].shape),
+                               rtol=2e-3, atol=0)
+
+
+def test_row_zero_returns_first_value_exactly():
+    q, k, v = synth.qkv(13, 70, 70, 4, 2)
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), 0, 0, True)
+    assert torch.equal(out[0].cpu(), v[0].repeat_interleave(2, dim=0))
+    ref = (q[0].double() * k[0].repeat_interleave(2, dim=0).double()).sum(-1) / math.sqrt(128.0)
+    np.testing.assert_allclose(lse[:, 0].cpu().numpy(), ref.numpy(), rtol=1e-3, atol=1e-3)
+
+
+def test_constant_value_is_reproduced():
+    q, k, _ = synth.qkv(14, 300, 300, 4, 4)
+    v = torch.full((300, 4, 128), -2.5, dtype=torch.bfloat16)
+    out, _ = pec.pec_attn_chunk(*gpu(q, k, v), 0, 0, True, out_dtype=torch.float32)
+    np.testing.assert_allclose(out.cpu().numpy(), -2.5, rtol=0, atol=2e-2)
+
+
+def test_gqa_is_bit_identical_to_mha_with_repeated_kv():
+    q, k, v = synth.qkv(15, 300, 400, 8, 2)
+    o_g, l_g = pec.pec_attn_chunk(*gpu(q, k, v), 150, 0, True)
+    kr, vr = k.repeat_interleave(4, dim=1).contiguous(), v.repeat_interleave(4, dim=1).contiguous()
+    o_m, l_m = pec.pec_attn_chunk(*gpu(q, kr, vr), 150, 0, True)
+    assert torch.equal(o_g, o_m) and torch.equal(l_g, l_m)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_merge_matches_oracle_and_identity_is_exact(dtype):
+    sq, hq = 333, 4
+    g = torch.Generator().manual_seed(16)
+    o_a = torch.randn(sq, hq, 128, generator=g).to(dtype)
+    o_b = torch.randn(sq, hq, 128, generator=g).to(dtype)
+    l_a = torch.randn(hq, sq, generator=g) * 3
+    l_b = torch.randn(hq, sq, generator=g) * 3
+    l_a[0, :7] = -math.inf          # rows known only to B
+    l_b[1, 5:9] = -math.inf         # rows known only to A
+    l_a[2, 100], l_b[2, 100] = -math.inf, -math.inf
+    o_a[:7, 0] = 0
+    o_b[5:9, 1] = 0
+    o_a[100, 2] = 0
+    o_b[100, 2] = 0
+    o_ref, l_ref = oracle.merge(o_a.double().numpy(), l_a.double().numpy(), o_b.double().numpy(),
+                                l_b.double().numpy())
+    o, lse = pec.pec_attn_merge(o_a.to(DEV).clone(), l_a.to(DEV).clone(), o_b.to(DEV), l_b.to(DEV))
+    assert_close(o, lse, o_ref, l_ref, "merge %s" % dtype)
+    # (0, -inf) is the identity, bit for bit, on either side
+    zero = torch.zeros_like(o_a).to(DEV)
+    ninf = torch.full_like(l_a, -math.inf).to(DEV)
+    o, lse = pec.pec_attn_merge(o_b.to(DEV).clone(), l_b.to(DEV).clone(), zero, ninf)
+    keep = torch.isfinite(l_b)
+    assert torch.equal(lse.cpu(), l_b)
+    assert torch.equal(o.cpu()[keep.T], o_b[keep.T])
+    o, lse = pec.pec_attn_merge(zero.clone(), ninf.clone(), o_b.to(DEV), l_b.to(DEV))
+    assert torch.equal(lse.cpu(), l_b) and torch.equal(o.cpu()[keep.T], o_b[keep.T])
+
+
+@pytest.mark.parametrize("variant", VARIANTS[:2])
+def test_chunk_merge_folds_segments_exactly(variant):
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
+    sq, s, hq, hkv, q_off = 300, 900, 4, 2, 600
+    q, k, v = synth.qkv(17, sq, s, hq, hkv)
+    o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
+    qd, kd, vd = gpu(q, k, v)
+    o_acc = torch.zeros(sq, hq, 128, dtype=torch.float32, device=DEV)
+    l_acc = torch.full((hq, sq), -math.inf, dtype=torch.float32, device=DEV)
+    final = torch.empty(sq, hq, 128, dtype=torch.bfloat16, device=DEV)
+    edges = [0, 250, 251, 640, 900]                 # uneven segments, one of a single key
+    order = [2, 0, 3, 1]                            # any order gives the same result
+    for n, c in enumerate(order):
+        lo, hi = edges[c], edges[c + 1]
+        pec.pec_attn_chunk_merge(qd, kd[lo:hi], vd[lo:hi], q_off, lo, o_acc, l_acc, True,
+                                 out_final=final if n == len(order) - 1 else None)
+    assert_close(o_acc, l_acc, o_ref, l_ref, "chunk_merge acc")
+    assert_close(final, l_acc, o_ref, l_ref, "chunk_merge final")
+    # separate-kernel route: fp32 partials + pec_attn_merge + pec_finalize
+    o2 = torch.zeros_like(o_acc)
+    l2 = torch.full_like(l_acc, -math.inf)
+    for c in order:
+        lo, hi = edges[c], edges[c + 1]
+        o_p, l_p = pec.pec_attn_chunk(qd, kd[lo:hi], vd[lo:hi], q_off, lo, True, out_dtype=torch.float32)
+        pec.pec_attn_merge(o2, l2, o_p, l_p)
+    assert_close(pec.pec_finalize(o2), l2, o_ref, l_ref, "chunk + merge + finalize")
+
+
+@pytest.mark.parametrize("mode", [pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SEPARATE_MERGE, pec.PEC_SP_SINGLE_LAUNCH])
+@pytest.mark.parametrize("variant", VARIANTS[:2])
+def test_sp_prefill_small_config_in_full(mode, variant):
+    """8 heads = 8 KV heads, seq 2048 as 4 segments of 512: every ring member, every row."""
+    w = synth.WORKLOADS["c1_mha_2k"]
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
+    pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
+    q, k, v = synth.qkv(w.seed, w.seq, w.seq, w.n_q_heads, w.n_kv_heads)
+    o_ref, l_ref = oracle.attention(q, k, v, causal=True)
+    qd, kd, vd = gpu(q, k, v)
+    for r in range(w.seq // w.chunk):
+        lo, hi = r * w.chunk, (r + 1) * w.chunk
+        out, lse = pec.pec_sp_prefill(qd[lo:hi], kd, vd, lo, w.chunk, True)
+        assert_close(out, lse, o_ref[lo:hi], l_ref[:, lo:hi], "sp_prefill c1 member %d mode %d" % (r, mode))
+
+
+@pytest.mark.parametrize("mode", [pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SEPARATE_MERGE])
+def test_sp_prefill_ragged_and_noncausal(mode):
+    pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
+    s, hq, hkv, chunk = 1000, 4, 2, 300                         # last segment has 100 tokens
+    q, k, v = synth.qkv(18, s, s, hq, hkv)
+    qd, kd, vd = gpu(q, k, v)
+    o_ref, l_ref = oracle.attention(q, k, v, causal=True)
+    for r in range(4):
+        lo, hi = r * chunk, min(s, (r + 1) * chunk)
+        out, lse = pec.pec_sp_prefill(qd[lo:hi], kd, vd, lo, chunk, True, out_dtype=torch.float32)
+        assert_close(out, lse, o_ref[lo:hi], l_ref[:, lo:hi], "ragged member %d" % r)
+    o_nc, l_nc = oracle.attention(q[300:600], k, v, causal=False)
+    out, lse = pec.pec_sp_prefill(qd[300:600], kd, vd, 300, chunk, False)
+    assert_close(out, lse, o_nc, l_nc, "non-causal ring")
+
+
+@pytest.mark.parametrize("variant", VARIANTS[:2])
+def test_varlen_matches_oracle_and_dense_calls(variant):
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
+    lengths = [5, 0, 1, 300, 257, 0, 64, 700, 256]
+    cu = synth.cu_seqlens_of(lengths)
+    t, hq, hkv = int(cu[-1]), 4, 2
+    q, k, v = synth.qkv(19, t, t, hq, hkv)
+    o_ref, l_ref = oracle.varlen(q, k, v, cu)
+    qd, kd, vd = gpu(q, k, v)
+    cud = torch.from_numpy(cu).to(DEV)
+    out, lse = pec.pec_attn_varlen(qd, kd, vd, cud, max(lengths), True)
+    assert_close(out, lse, o_ref, l_ref, "varlen")
+    for b, n in enumerate(lengths):                 # bit-identical to one dense call per sequence
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        if n == 0:
+            continue
+        o_b, l_b = pec.pec_attn_chunk(qd[lo:hi].contiguous(), kd[lo:hi].contiguous(), vd[lo:hi].contiguous(), 0, 0)
+        assert torch.equal(out[lo:hi], o_b) and torch.equal(lse[:, lo:hi], l_b), "sequence %d" % b
+    # Q = 0: LSE = ln(position + 1) exposes any leak across sequence boundaries
+    _, lse0 = pec.pec_attn_varlen(torch.zeros_like(qd), kd, vd, cud, max(lengths), True)
+    pos = np.concatenate([np.arange(n) for n in lengths])
+    got = np.rint(np.exp(lse0.cpu().numpy().astype(np.float64))).astype(np.int64)
+    assert np.array_equal(got, np.tile(pos + 1, (hq, 1)))
+
+
+def _sampled_check(qd, kd, vd, out, lse, q_off, rows, heads=None, what=""):
+    """Oracle on sampled rows against the full key range (rows are independent in Eq. 2-3)."""
+    g = qd.shape[1] // kd.shape[1]
+    rows_t = torch.from_numpy(rows).to(qd.device)
+    if heads is None:
+        qs, k_h, v_h = qd[rows_t].cpu(), kd.cpu(), vd.cpu()
+        o_s, l_s = out[rows_t], lse[:, rows_t]
+    else:                                             # one KV head and its query group
+        kvh = heads
+        hs = slice(kvh * g, (kvh + 1) * g)
+        qs, k_h, v_h = qd[rows_t][:, hs].cpu().contiguous(), kd[:, kvh:kvh + 1].cpu().contiguous(), \
+            vd[:, kvh:kvh + 1].cpu().contiguous()
+        o_s, l_s = out[rows_t][:, hs], lse[hs][:, rows_t]
+    o_ref, l_ref = oracle.attention(qs, k_h, v_h, q_pos=q_off + rows, kv_off=0, causal=True)
+    assert_close(o_s, l_s, o_ref, l_ref, what)
+
+
+def test_full_size_gqa_32k_last_member_sampled_rows():
+    """32 query / 8 KV heads, seq 32768 in 8 segments of 4096: the last ring member's share."""
+    w = synth.WORKLOADS["c2_gqa_32k"]
+    q_off = w.seq - w.chunk
+    q, k, v = synth.qkv(w.seed, w.chunk, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
+    rows = synth.sample_rows(w.seed, w.chunk, boundaries=(256, 2048), n_random=24)
+    for mode in (pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SINGLE_LAUNCH):
+        pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
+        out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
+        _sampled_check(q, k, v, out, lse, q_off, rows, what="c2 mode %d" % mode)
+
+
+def test_full_size_gqa_128k_sampled_rows():
+    """The headline shape: seq 131072 in 16 segments of 8192; members 15 (longest) and 6."""
+    w = synth.WORKLOADS["c3_gqa_128k"]
+    q_all, k, v = synth.qkv(w.seed, w.seq, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
+    for r, n_random in ((15, 10), (6, 10)):
+        q_off = r * w.chunk
+        q = q_all[q_off:q_off + w.chunk]
+        out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
+        rows = synth.sample_rows(w.seed + r, w.chunk, boundaries=(), n_random=n_random, edge=2)
+        _sampled_check(q, k, v, out, lse, q_off, rows, heads=r % w.n_kv_heads, what="c3 member %d" % r)
