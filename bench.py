@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the ring-style blockwise causal prefill attention path on one MI355X.
+
+A step is one full sequential ring sweep of the workload on one GPU: every query
+segment r = 0..P-1 runs pec_sp_prefill over the KV segments it can see, in ring
+order, with the log-sum-exp merge folded in at every step.  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen]
+                  [--sp-mode fused|separate|single] [--variant N] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 matrix peak: 256 CU x 4096 flop/clk x 2.4 GHz
+FLOP_PER_PAIR = 512.0          # per (query, key, head): 2*128 for q.k plus 2*128 for p.v
+# HBM bytes per dominant-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by
+# a copy kernel of known size); see profiles/.  None until measured for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3_gqa_128k")
+    ap.add_argument("--sp-mode", default="fused", choices=["fused", "separate", "single"])
+    ap.add_argument("--variant", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (nothing here spans devices); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2409_15104_amd import binding as pec
+    from paper_2409_15104_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    pec.lib()  # fails loudly when the HIP library has not been built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.variant is not None:
+        pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, args.variant)
+    mode = {"fused": pec.PEC_SP_FUSED_MERGE, "separate": pec.PEC_SP_SEPARATE_MERGE,
+            "single": pec.PEC_SP_SINGLE_LAUNCH}[args.sp_mode]
+    pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
+
+    if args.workload == "c4_varlen":
+        return bench_varlen(args, torch, np, pec, synth, dev)
+
+    w = synth.WORKLOADS[args.workload]
+    S, C, Hq, Hkv = w.seq, w.chunk, w.n_q_heads, w.n_kv_heads
+    P = S // C
+    q, k, v = synth.qkv(w.seed, S, S, Hq, Hkv, device=dev)
+    out = torch.empty_like(q)
+    lse = torch.empty((P, Hq, C), dtype=torch.float32, device=dev)   # one [Hq, C] block per ring member
+    ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C)), dtype=torch.uint8, device=dev)
+
+    pairs = sum(synth.visible_pairs(C, min(C, S - c * C), r * C, c * C, True)
+                for r in range(P) for c in range(r + 1))
+    assert pairs == S * (S + 1) // 2
+    flops = FLOP_PER_PAIR * Hq * pairs
+    launches = P * (P + 1) // 2 if mode != pec.PEC_SP_SINGLE_LAUNCH else P
+
+    def step():
+        for r in range(P):
+            lo = r * C
+            pec.pec_sp_prefill(q[lo:lo + C], k, v, lo, C, True, out=out[lo:lo + C], lse=lse[r], workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    ev_ms_step = ev0.elapsed_time(ev1) / args.steps
+    tflops = flops / (ms_step * 1e-3) / 1e12
+
+    # Dominant kernel = the attention kernel (every launch of the timed region in fused/single mode).
+    # Average launch duration from HIP events on the launch stream over the timed region.
+    avg_launch_ms = ev_ms_step / launches
+    achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "kernel": "pec::fwd_kernel", "launches_per_step": launches,
+                "avg_launch_ms": round(avg_launch_ms, 4), "flop_per_launch_avg": flops / launches}
+
+    result = {
+        "metric": "prefill attention TFLOP/s and tokens/s at 128K GQA; % of bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: causal prefill, %d q heads / %d kv heads, d 128, seq %d as %d segments of %d, "
+                               "full ring sweep with LSE merge (%s)" % (w.name, Hq, Hkv, S, P, C, args.sp_mode),
+                   "seq_len": S, "chunk": C, "n_q_heads": Hq, "n_kv_heads": Hkv, "sp_mode": args.sp_mode,
+                   "kernel_variant": pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)},
+        "tokens_per_s": round(S / (ms_step * 1e-3), 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "causal_useful_tflop_per_step": round(flops / 1e12, 3),
+        "noncausal_convention_tflops": round(4.0 * 128 * Hq * S * S / (ms_step * 1e-3) / 1e12, 2),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, np, torch, synth, q, k, v, w)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def cpu_baseline(args, np, torch, synth, q, k, v, w):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: whole rows
+    (all heads, full visible key range) drawn uniformly from the sequence."""
+    from oracle import reference as oracle
+
+    S, Hq = w.seq, w.n_q_heads
+    k_h, v_h = k.cpu(), v.cpu()
+    rng = np.random.default_rng(w.seed)
+
+    def run(n_rows):
+        rows = np.sort(rng.integers(0, S, size=n_rows))
+        qs = q[torch.from_numpy(rows).to(q.device)].cpu()
+        t0 = time.perf_counter()
+        oracle.attention(qs, k_h, v_h, q_pos=rows, kv_off=0, causal=True)
+        dt = time.perf_counter() - t0
+        return dt, int((rows + 1).sum())
+
+    dt, pairs = run(4)                                  # calibration, then the timed sample
+    rate = pairs / max(dt, 1e-6)
+    n_rows = int(max(4, min(4096, args.cpu_seconds * rate / (S / 2))))
+    dt, pairs = run(n_rows)
+    tflops = FLOP_PER_PAIR * Hq * pairs / dt / 1e12
+    full_pairs = S * (S + 1) // 2
+    return {"value": round(tflops, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d uniformly drawn query rows x %d heads over their full causal key range "
+                      "(%.3g visible pairs per head, %.1f s); full workload extrapolates to %.0f s"
+                      % (n_rows, Hq, pairs, dt, full_pairs / (pairs / dt)),
+            "tokens_per_s_extrapolated": round(S / (full_pairs / (pairs / dt)), 3)}
+
+
+def bench_varlen(args, torch, np, pec, synth, dev):
+    """Colocated batch: 256 log-normal short prompts + one 65,536-token prompt, one launch."""
+    Hq, Hkv = 32, 8
+    lengths = synth.varlen_lengths()
+    cu = synth.cu_seqlens_of(lengths)
+    T = int(cu[-1])
+    q, k, v = synth.qkv(synth.VARLEN_SEED, T, T, Hq, Hkv, device=dev)
+    cud = torch.from_numpy(cu).to(dev)
+    out = torch.empty_like(q)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=dev)
+    ws = torch.empty(pec.pec_varlen_workspace_bytes(len(lengths), T), dtype=torch.uint8, device=dev)
+    pairs = int(sum(int(n) * (int(n) + 1) // 2 for n in lengths))
+    flops = FLOP_PER_PAIR * Hq * pairs
+    max_len = int(lengths.max())
+
+    def step():
+        pec.pec_attn_varlen(q, k, v, cud, max_len, True, out=out, lse=lse, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    tflops = flops / (ms_step * 1e-3) / 1e12
+    ach = flops / (ev_ms * 1e-3) / 1e12
+    result = {
+        "metric": "prefill attention TFLOP/s and tokens/s at 128K GQA; % of bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_varlen: %d packed prompts (256 log-normal short + one 65536), %d tokens, "
+                               "32 q / 8 kv heads, causal per sequence" % (len(lengths), T), "total_tokens": T},
+        "tokens_per_s": round(T / (ms_step * 1e-3), 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": "pec::fwd_kernel"},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
