@@ -133,9 +133,12 @@ enum {
     PEC_OPT_SP_MODE = 1         /* see PEC_SP_* */
 };
 enum {
-    PEC_VARIANT_W4_Q64 = 0,      /* 4 wavefronts x 64 query rows, transposing LDS reads for V (default) */
-    PEC_VARIANT_W8_Q32 = 1,      /* 8 wavefronts x 32 query rows */
-    PEC_VARIANT_W4_Q64_NOTR = 2  /* as 0 but V operands gathered with scalar LDS reads (slow; cross-check) */
+    PEC_VARIANT_W4_Q64 = 0,      /* register-staged tiles: 4 wavefronts x 64 query rows */
+    PEC_VARIANT_W8_Q32 = 1,      /* register-staged tiles: 8 wavefronts x 32 query rows */
+    PEC_VARIANT_W4_Q64_NOTR = 2, /* as 0 but V operands gathered with scalar LDS reads (slow; cross-check) */
+    PEC_VARIANT_DMA_W8_Q32 = 3,  /* direct global->LDS tiles: 8 wavefronts x 32 query rows (default) */
+    PEC_VARIANT_DMA_W4_Q32 = 4,  /* direct global->LDS tiles: 4 wavefronts x 32 rows, 128-row workgroups */
+    PEC_VARIANT_DMA_W4_Q64 = 5   /* direct global->LDS tiles: 4 wavefronts x 64 query rows */
 };
 enum {
     PEC_SP_FUSED_MERGE = 0,   /* one pec_attn_chunk_merge launch per ring step (default) */

@@ -10,19 +10,41 @@
 
 #include "aux_kernels.hpp"
 #include "fwd_kernel.hpp"
+#include "fwd_kernel_dma.hpp"
 
 namespace {
 
 using namespace pec;
 
-enum { VARIANT_W4_Q64 = 0, VARIANT_W8_Q32 = 1, VARIANT_W4_Q64_NOTR = 2, N_VARIANTS = 3 };
+// Kernel variants (PEC_VARIANT_*): query rows per workgroup and the launcher.
+typedef void (*launch_fn)(const FwdParams&, unsigned grid, hipStream_t);
+template <int NT, int NWAVES, bool TR>
+void launch_v1(const FwdParams& p, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL((fwd_kernel<NT, NWAVES, TR>), dim3(grid), dim3(NWAVES * 64), 0, st, p);
+}
+template <int NT, int NWAVES>
+void launch_dma(const FwdParams& p, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL((fwd_dma_kernel<NT, NWAVES>), dim3(grid), dim3(NWAVES * 64), 0, st, p);
+}
+struct Variant {
+    int bm;
+    launch_fn launch;
+};
+const Variant kVariants[] = {
+    {256, launch_v1<2, 4, true>},   // PEC_VARIANT_W4_Q64
+    {256, launch_v1<1, 8, true>},   // PEC_VARIANT_W8_Q32
+    {256, launch_v1<2, 4, false>},  // PEC_VARIANT_W4_Q64_NOTR
+    {256, launch_dma<1, 8>},        // PEC_VARIANT_DMA_W8_Q32
+    {128, launch_dma<1, 4>},        // PEC_VARIANT_DMA_W4_Q32
+    {256, launch_dma<2, 4>},        // PEC_VARIANT_DMA_W4_Q64
+};
+constexpr int N_VARIANTS = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-int g_variant = VARIANT_W4_Q64;
+int g_variant = PEC_VARIANT_DMA_W8_Q32;
 int g_sp_mode = PEC_SP_FUSED_MERGE;
 
 constexpr int64_t kMaxRows = (int64_t)1 << 30;
-constexpr int kBM = 256;           // query rows per workgroup, the same for every variant
-constexpr int kMinBM = 128;        // used only to bound work-list sizes
+constexpr int kMinBM = 128;        // smallest query tile of any variant; bounds work-list sizes
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -44,17 +66,7 @@ int launch_fwd(const FwdParams& p, hipStream_t stream) {
     const int64_t per_xcd = (total + 7) / 8;
     const int64_t grid = per_xcd * 8;
     if (grid > 0x7fffffffLL) return PEC_ERR_UNSUPPORTED;
-    switch (g_variant) {
-        case VARIANT_W4_Q64:
-            hipLaunchKernelGGL((fwd_kernel<2, 4, true>), dim3((unsigned)grid), dim3(256), 0, stream, p);
-            break;
-        case VARIANT_W8_Q32:
-            hipLaunchKernelGGL((fwd_kernel<1, 8, true>), dim3((unsigned)grid), dim3(512), 0, stream, p);
-            break;
-        default:
-            hipLaunchKernelGGL((fwd_kernel<2, 4, false>), dim3((unsigned)grid), dim3(256), 0, stream, p);
-            break;
-    }
+    kVariants[g_variant].launch(p, (unsigned)grid, stream);
     return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
 }
 
@@ -91,7 +103,8 @@ int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const voi
     p.n_q_heads = shape->n_q_heads;
     p.n_kv_heads = shape->n_kv_heads;
     p.group = shape->n_q_heads / shape->n_kv_heads;
-    p.n_items = (int32_t)((sq + kBM - 1) / kBM);
+    const int bm = kVariants[g_variant].bm;
+    p.n_items = (int32_t)((sq + bm - 1) / bm);
     p.out_f32 = out_f32;
     p.scale_log2 = scale * kLog2e;
     return launch_fwd(p, static_cast<hipStream_t>(stream));
@@ -271,6 +284,7 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
     if (!workspace || workspace_bytes < pec_varlen_workspace_bytes(batch, total_tokens)) return PEC_ERR_WORKSPACE;
 
     const int64_t max_len = std::min<int64_t>(max_seqlen, total_tokens);
+    const int kBM = kVariants[g_variant].bm;
     const int max_qtiles = (int)((max_len + kBM - 1) / kBM);
     // every sequence contributes at most len/BM + 1 items
     const int64_t cap64 = total_tokens / kBM + batch;

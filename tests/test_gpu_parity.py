@@ -19,12 +19,14 @@ pytestmark = pytest.mark.gpu
 O_ATOL = 2e-2
 LSE_RTOL = 1e-3
 DEV = "cuda:0"
-VARIANTS = [pec.PEC_VARIANT_W4_Q64, pec.PEC_VARIANT_W8_Q32, pec.PEC_VARIANT_W4_Q64_NOTR]
+# default first; the last one is the slow cross-check kernel (kept out of the heavier tests)
+VARIANTS = [pec.PEC_VARIANT_DMA_W8_Q32, pec.PEC_VARIANT_DMA_W4_Q64, pec.PEC_VARIANT_DMA_W4_Q32, pec.PEC_VARIANT_W8_Q32,
+            pec.PEC_VARIANT_W4_Q64, pec.PEC_VARIANT_W4_Q64_NOTR]
 
 
 @pytest.fixture(autouse=True)
 def _defaults():
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, pec.PEC_VARIANT_W4_Q64)
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, pec.PEC_VARIANT_DEFAULT)
     pec.pec_set_option(pec.PEC_OPT_SP_MODE, pec.PEC_SP_FUSED_MERGE)
     yield
     torch.cuda.synchronize()
@@ -83,7 +85,7 @@ def test_chunk_empty_query_is_a_noop():
     assert out.shape == (0, 2, 128) and lse.shape == (2, 0)
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:2])
+@pytest.mark.parametrize("variant", VARIANTS[:4])
 @pytest.mark.parametrize("q_off,kv_off,sq,sk", [(0, 0, 600, 600), (1000, 937, 333, 700), (5, 200, 300, 90),
                                                (0, 64, 256, 256), (255, 0, 258, 515)])
 def test_mask_is_bit_exact_via_zero_query(q_off, kv_off, sq, sk, variant):
@@ -162,7 +164,7 @@ def test_merge_matches_oracle_and_identity_is_exact(dtype):
     assert torch.equal(lse.cpu(), l_b) and torch.equal(o.cpu()[keep.T], o_b[keep.T])
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:2])
+@pytest.mark.parametrize("variant", VARIANTS[:4])
 def test_chunk_merge_folds_segments_exactly(variant):
     pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     sq, s, hq, hkv, q_off = 300, 900, 4, 2, 600
@@ -191,7 +193,7 @@ def test_chunk_merge_folds_segments_exactly(variant):
 
 
 @pytest.mark.parametrize("mode", [pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SEPARATE_MERGE, pec.PEC_SP_SINGLE_LAUNCH])
-@pytest.mark.parametrize("variant", VARIANTS[:2])
+@pytest.mark.parametrize("variant", VARIANTS[:4])
 def test_sp_prefill_small_config_in_full(mode, variant):
     """8 heads = 8 KV heads, seq 2048 as 4 segments of 512: every ring member, every row."""
     w = synth.WORKLOADS["c1_mha_2k"]
@@ -222,7 +224,7 @@ def test_sp_prefill_ragged_and_noncausal(mode):
     assert_close(out, lse, o_nc, l_nc, "non-causal ring")
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:2])
+@pytest.mark.parametrize("variant", VARIANTS[:4])
 def test_varlen_matches_oracle_and_dense_calls(variant):
     pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     lengths = [5, 0, 1, 300, 257, 0, 64, 700, 256]
