@@ -11,6 +11,7 @@
 #include "aux_kernels.hpp"
 #include "fwd_kernel.hpp"
 #include "fwd_kernel_dma.hpp"
+#include "fwd_kernel_pp.hpp"
 
 namespace {
 
@@ -26,6 +27,14 @@ template <int NT, int NWAVES>
 void launch_dma(const FwdParams& p, unsigned grid, hipStream_t st) {
     hipLaunchKernelGGL((fwd_dma_kernel<NT, NWAVES>), dim3(grid), dim3(NWAVES * 64), 0, st, p);
 }
+template <bool PAIR_STRIDE4>
+void launch_pp(const FwdParams& p, unsigned grid, hipStream_t st) {
+    // 96 KiB of dynamic LDS is above the default limit: raise it once per process
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_pp_kernel<PAIR_STRIDE4>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPpLdsBytes);
+    (void)attr;
+    hipLaunchKernelGGL((fwd_pp_kernel<PAIR_STRIDE4>), dim3(grid), dim3(512), kPpLdsBytes, st, p);
+}
 struct Variant {
     int bm;
     launch_fn launch;
@@ -37,6 +46,8 @@ const Variant kVariants[] = {
     {256, launch_dma<1, 8>},        // PEC_VARIANT_DMA_W8_Q32
     {128, launch_dma<1, 4>},        // PEC_VARIANT_DMA_W4_Q32
     {256, launch_dma<2, 4>},        // PEC_VARIANT_DMA_W4_Q64
+    {256, launch_pp<true>},         // PEC_VARIANT_PINGPONG
+    {256, launch_pp<false>},        // PEC_VARIANT_PINGPONG_ADJ
 };
 constexpr int N_VARIANTS = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
