@@ -19,7 +19,7 @@ PEC_BF16, PEC_F32 = 0, 1
 PEC_OPT_KERNEL_VARIANT, PEC_OPT_SP_MODE = 0, 1
 PEC_VARIANT_W4_Q64, PEC_VARIANT_W8_Q32, PEC_VARIANT_W4_Q64_NOTR = 0, 1, 2
 PEC_VARIANT_DMA_W8_Q32, PEC_VARIANT_DMA_W4_Q32, PEC_VARIANT_DMA_W4_Q64 = 3, 4, 5
-PEC_VARIANT_PINGPONG, PEC_VARIANT_PINGPONG_ADJ = 6, 7
+PEC_VARIANT_PINGPONG, PEC_VARIANT_PINGPONG_ADJ, PEC_VARIANT_INTERLEAVED = 6, 7, 8
 PEC_VARIANT_DEFAULT = PEC_VARIANT_DMA_W8_Q32
 PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
 

@@ -1,0 +1,453 @@
+// Blockwise attention forward kernel with MFMA and softmax interleaved inside every
+// wavefront's instruction stream (gfx950).
+//
+// Measurements on MI355X behind this organisation: a wavefront that issues MFMAs back
+// to back keeps the vector ALU of its SIMD from serving the other resident wavefront,
+// so running softmax in one wavefront while another does MFMAs gains nothing; but VALU
+// instructions that FOLLOW an MFMA in the same wavefront do execute under it.  So the
+// tile loop is software-pipelined in each wavefront: iteration j carries
+//     S(j+1) = K(j+1) Q^T               16 MFMAs
+//     O     += P(j-1) V(j-1)            16 MFMAs   (P(j-1) from the previous iteration)
+//     P(j)   = exp2(S(j) - m(j)) etc.   ~115 VALU  (S(j), m(j) from the previous iteration)
+//     m(j+1), alpha(j+1) from S(j+1)    ~25 VALU   (after the first 16 MFMAs)
+// which are independent of each other and get issued round-robin (about 4 VALU per MFMA).
+// Same MFMA operand layouts, LDS swizzles and direct global->LDS tile loads as
+// fwd_kernel_dma.hpp; 8 wavefronts x 32 query rows; one workgroup barrier per tile.
+//
+// LDS: two stages each for K and V, declared as four separate arrays so that the
+// compiler can prove that the stage the tile loads write is never the one being read
+// (otherwise it waits for the loads before every LDS read).  Iteration j, parity
+// r = j % 2: loads K(j+2) -> K[r] and V(j) -> V[r]; reads K(j+1) from K[1-r] and V(j-1)
+// from V[1-r].  The loop is unrolled by two so that every access names its array.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "fwd_kernel.hpp"
+#include "fwd_kernel_dma.hpp"
+
+namespace pec {
+
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+__device__ __forceinline__ void scale_acc_in_place(f32x16& x, float a) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x[r]) : "v"(a));
+}
+
+__global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
+    constexpr int NWAVES = 8;
+    constexpr int BM = NWAVES * 32;
+
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_k0[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_k1[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_v0[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_v1[kTileBytes];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int hl = lane >> 5;
+
+    // ---- block -> (kv head, work item, head in group), one contiguous logical range per XCD
+    const int64_t total = (int64_t)p.n_items * p.n_q_heads;
+    const int64_t per_xcd = (total + 7) >> 3;
+    const int64_t logical = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total) return;
+    const int per_kvh = p.n_items * p.group;
+    const int kvh = (int)(logical / per_kvh);
+    const int rem = (int)(logical % per_kvh);
+    const int item = rem / p.group;
+    const int head = kvh * p.group + rem % p.group;
+
+    int sq, sk, delta, qt;
+    int64_t q_tok0, kv_tok0;
+    if (p.cu_seqlens) {
+        if (item >= *p.n_work) return;
+        const WorkItem w = p.work[item];
+        const int b0 = min(max(p.cu_seqlens[w.seq], 0), p.total_tokens);
+        const int b1 = min(max(p.cu_seqlens[w.seq + 1], b0), p.total_tokens);
+        sq = sk = b1 - b0;
+        delta = 0;
+        qt = w.qtile;
+        q_tok0 = kv_tok0 = b0;
+    } else {
+        sq = p.sq;
+        sk = p.sk;
+        delta = p.delta;
+        qt = p.causal ? (p.n_items - 1 - item) : item;  // longest rows first
+        q_tok0 = kv_tok0 = 0;
+    }
+    const int causal = p.causal;
+    const int row0 = qt * BM;
+    const int rw0 = row0 + wave * 32;
+    const int wave_last = rw0 + 31;
+    const int blk_last = min(sq, row0 + BM) - 1;
+    int kv_end = sk;
+    if (causal) kv_end = max(0, min(sk, blk_last + delta + 1));
+    const int n_tiles = (kv_end + kBN - 1) / kBN;
+
+    // runs of tiles for this wavefront: [0, n_full) need no mask, [n_full, n_act) do,
+    // [n_act, n_tiles) lie wholly after its rows (causal only)
+    int n_full = sk / kBN;
+    int n_act = n_tiles;
+    if (causal) {
+        n_full = min(n_full, max(0, rw0 + delta + 1) / kBN);
+        n_act = min(n_tiles, max(0, wave_last + delta + kBN) / kBN);
+    }
+    n_full = min(n_full, n_tiles);
+    n_act = max(n_act, n_full);
+
+    const int64_t q_stride = (int64_t)p.n_q_heads * kHeadDim;
+    const uint32_t kv_stride_b = (uint32_t)p.n_kv_heads * kHeadDim * 2;   // bytes per token
+    const unsigned char* kbase =
+        reinterpret_cast<const unsigned char*>(p.k) + (kv_tok0 * p.n_kv_heads + kvh) * (int64_t)(kHeadDim * 2);
+    const unsigned char* vbase =
+        reinterpret_cast<const unsigned char*>(p.v) + (kv_tok0 * p.n_kv_heads + kvh) * (int64_t)(kHeadDim * 2);
+
+    // ---- Q fragments
+    bf16x8 qf[8];
+    {
+        const int row = rw0 + l32;
+        const __bf16* qrow = p.q + (q_tok0 + row) * q_stride + (int64_t)head * kHeadDim + 8 * hl;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (row < sq) raw = *reinterpret_cast<const u32x4*>(qrow + 16 * t);
+            qf[t] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    // ---- running state
+    f32x16 o[4];
+    float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    if (p.acc_in) {
+        const int row = rw0 + l32;
+        if (row < sq) {
+            const float lin = p.lse_in[(int64_t)head * p.lse_stride + q_tok0 + row];
+            if (lin != -INFINITY) {
+                m_run = lin * kLog2e;
+                l_run = hl == 0 ? 1.f : 0.f;
+                const float* arow = p.acc_in + (q_tok0 + row) * q_stride + (int64_t)head * kHeadDim + 4 * hl;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const f32x4 x = *reinterpret_cast<const f32x4*>(arow + 32 * dt + 8 * b);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o[dt][4 * b + i] = x[i];
+                    }
+            }
+        }
+    }
+
+    // ---- tile loads: per tile and matrix each wavefront fills two 1 KiB LDS blocks of 4 key rows;
+    // lane s lands at byte 16*s of its block and fetches the chunk the swizzle wants there.
+    const int ld_row = lane >> 4, ld_pos = lane & 15;
+    int ld_key[2];
+    uint32_t ldk_col[2], ldv_col[2], ldk_off[2], ldv_off[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int key = 4 * (it * NWAVES + wave) + ld_row;
+        ld_key[it] = key;
+        ldk_col[it] = (uint32_t)(ld_pos ^ (key & 15)) * 16u;
+        ldv_col[it] = (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u;
+        ldk_off[it] = (uint32_t)key * kv_stride_b + ldk_col[it];
+        ldv_off[it] = (uint32_t)key * kv_stride_b + ldv_col[it];
+    }
+    auto issue_tile = [&](const unsigned char* base, const uint32_t (&col)[2], const uint32_t (&full_off)[2], int tile,
+                          unsigned char* __restrict__ stage) {
+        if (tile >= n_tiles) return;
+        const int key0 = tile * kBN;
+        const int last = sk - 1 - key0;   // rows past the end re-read the last valid row: finite, weight zero
+        const unsigned char* tb = base + (int64_t)key0 * kv_stride_b;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            uint32_t off = full_off[it];
+            if (last < kBN - 1) off = (uint32_t)min(ld_key[it], last) * kv_stride_b + col[it];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tb + off),
+                                             (__attribute__((address_space(3))) void*)(stage + (it * NWAVES + wave) * 1024),
+                                             16, 0, 0);
+        }
+    };
+    auto issue_k = [&](int tile, unsigned char* stage) { issue_tile(kbase, ldk_col, ldk_off, tile, stage); };
+    auto issue_v = [&](int tile, unsigned char* stage) { issue_tile(vbase, ldv_col, ldv_off, tile, stage); };
+
+    // ---- LDS operand offsets inside a stage
+    uint32_t k_off[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) k_off[t] = k_lds_off(l32, 2 * t + hl);
+    uint32_t v_off[4];
+    {
+        const int gi = l32 & 15, gg = l32 >> 4;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) v_off[dt] = v_lds_off(4 * hl + (gi >> 2), dt * 64 + gg * 32 + (gi & 3) * 8);
+    }
+
+    const float sl2 = p.scale_log2;
+    f32x16 s_a[2], s_b[2];        // score tiles of even / odd iterations
+    bf16x8 p_a[2][2], p_b[2][2];  // probability operands produced by even / odd iterations
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            p_a[i][k2] = __builtin_bit_cast(bf16x8, z);
+            p_b[i][k2] = __builtin_bit_cast(bf16x8, z);
+        }
+
+    auto qk_mfma = [&](f32x16 (&s)[2], const unsigned char* kst) {
+        bf16x8 kf[8][2];
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                kf[t][mt] = *reinterpret_cast<const bf16x8*>(kst + k_off[t] + mt * 32 * kRowBytes);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][mt], qf[t], s[mt], 0, 0, 0);
+    };
+    auto pv_mfma = [&](const bf16x8 (&pp)[2][2], const unsigned char* vst) {
+        bf16x8 vf[4][4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const unsigned char* src = vst + v_off[dt] + ks * 16 * kRowBytes;
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(src));
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                    (__attribute__((address_space(3))) bf16x4*)(src + 8 * kRowBytes));
+                vf[ks][dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks][dt], pp[ks >> 1][ks & 1], o[dt], 0, 0, 0);
+    };
+    // Softmax, split in two so that every iteration has VALU work that is ready from its first
+    // cycle.  row_max(): mask / row maximum of a fresh score tile -> new running maximum and the
+    // factor alpha by which everything accumulated so far shrinks.  weights(): exp2 of a score
+    // tile against the maximum fixed one iteration earlier -> P operands and the denominator.
+    float m_use = 0.f;    // maximum the pending tile's weights are taken against (0 for a row without keys)
+    float alpha = 1.f;    // exp2(previous maximum - m_use)
+    auto row_max = [&](auto mask_tag, f32x16 (&s)[2], int key0) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        if constexpr (MASK) {
+            const int row = rw0 + l32;
+            int last_vis = sk - 1;
+            if (causal) last_vis = min(last_vis, row + delta);
+            const int lim = last_vis - key0 - 4 * hl;   // compare against 32*mt + 8*(r/4) + r%4
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (mt * 32 + 8 * (r >> 2) + (r & 3) > lim) s[mt][r] = -INFINITY;
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+        {   // the other lane half holds the other 32 keys of the same query
+            const uint32_t u = __builtin_bit_cast(uint32_t, mx);
+            const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+            mx = fmaxf(__builtin_bit_cast(float, (uint32_t)sw[0]), __builtin_bit_cast(float, (uint32_t)sw[1]));
+        }
+        const float m_new = fmaxf(m_run, mx * sl2);
+        m_use = m_new;
+        if constexpr (MASK) m_use = (m_new == -INFINITY) ? 0.f : m_new;   // only masked tiles can leave a row empty
+        alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+    };
+    auto weights = [&](const f32x16 (&s)[2], bf16x8 (&pp)[2][2]) {
+        float rs = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                u32x4 packed;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f32x2 x = {__builtin_amdgcn_exp2f(fmaf(s[mt][8 * t2 + 2 * e], sl2, -m_use)),
+                                     __builtin_amdgcn_exp2f(fmaf(s[mt][8 * t2 + 2 * e + 1], sl2, -m_use))};
+                    rs += x[0] + x[1];   // denominator from the unrounded weights (LSE tolerance)
+                    packed[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+                }
+                pp[mt][t2] = __builtin_bit_cast(bf16x8, packed);
+            }
+        l_run = l_run * alpha + rs;
+    };
+
+    auto end_of_iteration = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's tile loads have landed
+        __builtin_amdgcn_s_barrier();
+    };
+
+    // One pipelined iteration j, parity PAR = j % 2:
+    //   MFMA : S(j+1) = K(j+1) Q^T (if DO_QK), then O += P(j-1) V(j-1)
+    //   VALU : P(j) = weights of S(j); then (if DO_QK) mask / row maximum of S(j+1)
+    //   last : O *= alpha(j), once the MFMAs above are done and before P(j) V(j) is added
+    auto body = [&](auto par_tag, auto mask_next_tag, auto qk_tag, int j) {
+        constexpr int PAR = decltype(par_tag)::value;
+        constexpr bool DO_QK = decltype(qk_tag)::value;
+        unsigned char* k_wr = PAR ? lds_k1 : lds_k0;
+        unsigned char* v_wr = PAR ? lds_v1 : lds_v0;
+        const unsigned char* k_rd = PAR ? lds_k0 : lds_k1;
+        const unsigned char* v_rd = PAR ? lds_v0 : lds_v1;
+        issue_k(j + 2, k_wr);
+        issue_v(j, v_wr);
+        const float alpha_j = alpha;
+        if constexpr (PAR == 0) {
+            if constexpr (DO_QK) qk_mfma(s_b, k_rd);
+            pv_mfma(p_b, v_rd);
+            weights(s_a, p_a);
+            if constexpr (DO_QK) row_max(mask_next_tag, s_b, (j + 1) * kBN);
+            asm volatile("" : "+v"(l_run), "+v"(m_run), "+v"(m_use), "+v"(alpha)
+                         : "v"(p_a[0][0]), "v"(p_a[0][1]), "v"(p_a[1][0]), "v"(p_a[1][1]));
+        } else {
+            if constexpr (DO_QK) qk_mfma(s_a, k_rd);
+            pv_mfma(p_a, v_rd);
+            weights(s_b, p_b);
+            if constexpr (DO_QK) row_max(mask_next_tag, s_a, (j + 1) * kBN);
+            asm volatile("" : "+v"(l_run), "+v"(m_run), "+v"(m_use), "+v"(alpha)
+                         : "v"(p_b[0][0]), "v"(p_b[0][1]), "v"(p_b[1][0]), "v"(p_b[1][1]));
+        }
+        // issue order: operand fragments a few MFMAs ahead; after every MFMA a slice of the softmax
+        if constexpr (DO_QK) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+            for (int i = 0; i < 10; ++i) {   // QK MFMAs, remaining K fragments
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {   // last QK MFMAs and first PV MFMAs, V fragments
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+            }
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+            for (int i = 0; i < 12; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            }
+        }
+        if (__any(alpha_j != 1.f)) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha_j);
+        }
+        end_of_iteration();
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+
+    // ---- prologue: K(0), K(1); V(0) also into the stage iteration 0 reads with P = 0 (finite data)
+    issue_k(0, lds_k0);
+    issue_k(1, lds_k1);
+    issue_v(0, lds_v1);
+    end_of_iteration();
+    if (n_act > 0) {
+        qk_mfma(s_a, lds_k0);
+        row_max(T{}, s_a, 0);
+    }
+    asm volatile("" : "+v"(s_a[0]), "+v"(s_a[1]), "+v"(m_run), "+v"(m_use), "+v"(alpha));
+    __builtin_amdgcn_s_barrier();     // K stage 0 may be overwritten from here on
+
+    // ---- schedule: every wavefront passes one barrier per tile.  Iteration j needs the mask
+    // for tile j + 1, so the unmasked run ends one tile early; it is taken in whole pairs.
+    int j = 0;
+    const int e1 = max(0, min(n_full - 1, n_act - 1)) & ~1;
+    for (; j < e1; j += 2) {
+        body(P0{}, F{}, T{}, j);
+        body(P1{}, F{}, T{}, j + 1);
+    }
+    for (; j + 1 < n_act - 1; j += 2) {
+        body(P0{}, T{}, T{}, j);
+        body(P1{}, T{}, T{}, j + 1);
+    }
+    if (j < n_act - 1) {
+        body(P0{}, T{}, T{}, j);
+        ++j;
+    }
+    if (n_act > 0) {   // last active tile (no further scores), then the product still owed
+        if (j & 1) {
+            body(P1{}, T{}, F{}, j);
+            pv_mfma(p_b, lds_v1);
+        } else {
+            body(P0{}, T{}, F{}, j);
+            pv_mfma(p_a, lds_v0);
+        }
+        ++j;
+    }
+    for (; j < n_tiles; ++j) {   // keep the workgroup's load / barrier cadence
+        issue_k(j + 2, (j & 1) ? lds_k1 : lds_k0);
+        issue_v(j, (j & 1) ? lds_v1 : lds_v0);
+        end_of_iteration();
+    }
+
+    // ---- epilogue
+    {
+        const int row = rw0 + l32;
+        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        if (row < sq) {
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+            if (hl == 0) p.lse[(int64_t)head * p.lse_stride + q_tok0 + row] = lse;
+            const int64_t obase = (q_tok0 + row) * q_stride + (int64_t)head * kHeadDim + 4 * hl;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    f32x4 x;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) x[i] = o[dt][4 * b + i] * inv;
+                    const int64_t idx = obase + 32 * dt + 8 * b;
+                    if (p.acc_out) *reinterpret_cast<f32x4*>(p.acc_out + idx) = x;
+                    if (p.out) {
+                        if (p.out_f32)
+                            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = x;
+                        else
+                            *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + idx) =
+                                __builtin_convertvector(x, bf16x4);
+                    }
+                }
+        }
+    }
+}
+
+}  // namespace pec

@@ -11,6 +11,7 @@
 #include "aux_kernels.hpp"
 #include "fwd_kernel.hpp"
 #include "fwd_kernel_dma.hpp"
+#include "fwd_kernel_il.hpp"
 #include "fwd_kernel_pp.hpp"
 
 namespace {
@@ -35,6 +36,9 @@ void launch_pp(const FwdParams& p, unsigned grid, hipStream_t st) {
     (void)attr;
     hipLaunchKernelGGL((fwd_pp_kernel<PAIR_STRIDE4>), dim3(grid), dim3(512), kPpLdsBytes, st, p);
 }
+void launch_il(const FwdParams& p, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL(fwd_il_kernel, dim3(grid), dim3(512), 0, st, p);
+}
 struct Variant {
     int bm;
     launch_fn launch;
@@ -48,6 +52,7 @@ const Variant kVariants[] = {
     {256, launch_dma<2, 4>},        // PEC_VARIANT_DMA_W4_Q64
     {256, launch_pp<true>},         // PEC_VARIANT_PINGPONG
     {256, launch_pp<false>},        // PEC_VARIANT_PINGPONG_ADJ
+    {256, launch_il},               // PEC_VARIANT_INTERLEAVED
 };
 constexpr int N_VARIANTS = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 

@@ -20,7 +20,7 @@ O_ATOL = 2e-2
 LSE_RTOL = 1e-3
 DEV = "cuda:0"
 # default first; the last one is the slow cross-check kernel (kept out of the heavier tests)
-VARIANTS = [pec.PEC_VARIANT_PINGPONG, pec.PEC_VARIANT_PINGPONG_ADJ, pec.PEC_VARIANT_DMA_W8_Q32, pec.PEC_VARIANT_DMA_W4_Q64, pec.PEC_VARIANT_DMA_W4_Q32, pec.PEC_VARIANT_W8_Q32,
+VARIANTS = [pec.PEC_VARIANT_INTERLEAVED, pec.PEC_VARIANT_PINGPONG, pec.PEC_VARIANT_PINGPONG_ADJ, pec.PEC_VARIANT_DMA_W8_Q32, pec.PEC_VARIANT_DMA_W4_Q64, pec.PEC_VARIANT_DMA_W4_Q32, pec.PEC_VARIANT_W8_Q32,
             pec.PEC_VARIANT_W4_Q64, pec.PEC_VARIANT_W4_Q64_NOTR]
 
 
