@@ -23,9 +23,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 matrix peak: 256 CU x 4096 flop/clk x 2.4 GHz
 FLOP_PER_PAIR = 512.0          # per (query, key, head): 2*128 for q.k plus 2*128 for p.v
-# HBM bytes per dominant-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by
-# a copy kernel of known size); see profiles/.  None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernel (read + written), averaged over the launches of one sweep,
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a device copy of known size
+# (profiles/fwd_kernel_c3_gqa_128k_hbm_traffic.md).  None where not measured.
+MEASURED_TRAFFIC_BYTES = {"c3_gqa_128k": 4.464e8}
 
 
 def parse_args():
@@ -38,6 +39,8 @@ def parse_args():
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run three 1 GiB device-to-device copies (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -56,6 +59,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.copy_probe:   # known traffic: 2^30 bytes read and 2^30 bytes written per copy
+        x = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": "3 device copies of 1073741824 bytes"}))
+        return 0
     pec.lib()  # fails loudly when the HIP library has not been built
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -108,7 +119,7 @@ def main():
     achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                "kernel": "pec::fwd_kernel", "launches_per_step": launches,
+                "kernel": "pec::fwd_dma_kernel<1, 8>", "launches_per_step": launches,
                 "avg_launch_ms": round(avg_launch_ms, 4), "flop_per_launch_avg": flops / launches}
 
     result = {
