@@ -215,7 +215,7 @@ def bench_varlen(args, torch, np, pec, synth, dev):
         "tokens_per_s": round(T / (ms_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": "pec::fwd_kernel"},
+                     "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": "pec::fwd_dma_kernel<1, 8>"},
     }
     print(json.dumps(result), flush=True)
     return 0

@@ -288,3 +288,35 @@ def test_full_size_gqa_128k_sampled_rows():
         out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
         rows = synth.sample_rows(w.seed + r, w.chunk, boundaries=(), n_random=n_random, edge=2)
         _sampled_check(q, k, v, out, lse, q_off, rows, heads=r % w.n_kv_heads, what="c3 member %d" % r)
+
+
+def test_full_size_colocated_varlen_batch_sampled_rows():
+    """256 log-normal short prompts + one 65,536-token prompt, packed; the long prompt first, in the
+    middle and last.  Sampled rows of the long prompt and of a few short ones against the oracle."""
+    hq, hkv = 32, 8
+    for where in ("last", "first", "middle"):
+        lengths = synth.varlen_lengths(long_at=where)
+        cu = synth.cu_seqlens_of(lengths)
+        total = int(cu[-1])
+        q, k, v = synth.qkv(synth.VARLEN_SEED, total, total, hq, hkv, device=DEV)
+        out, lse = pec.pec_attn_varlen(q, k, v, torch.from_numpy(cu).to(DEV), int(lengths.max()), True)
+        b_long = int(np.argmax(lengths))
+        picks = [b_long] + [int(b) for b in np.random.default_rng(5).choice(len(lengths), size=4, replace=False)]
+        for b in picks:
+            lo, n = int(cu[b]), int(lengths[b])
+            rows = synth.sample_rows(b, n, boundaries=(256,) if n > 300 else (), n_random=8, edge=2)
+            kvh = b % hkv
+            _sampled_check(q[lo:lo + n], k[lo:lo + n], v[lo:lo + n], out[lo:lo + n], lse[:, lo:lo + n], 0, rows,
+                           heads=kvh, what="c4 %s seq %d (len %d)" % (where, b, n))
+        del q, k, v, out, lse
+
+
+def test_full_size_gqa_512k_last_member_sampled_rows():
+    """64 query / 8 KV heads, seq 524288 in 32 segments of 16384: the last ring member's share
+    (16384 query rows against 2.1 GB of K/V)."""
+    w = synth.WORKLOADS["c5_gqa_512k"]
+    q_off = w.seq - w.chunk
+    q, k, v = synth.qkv(w.seed, w.chunk, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
+    out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
+    rows = synth.sample_rows(w.seed, w.chunk, boundaries=(), n_random=6, edge=1)
+    _sampled_check(q, k, v, out, lse, q_off, rows, heads=3, what="c5 last member")
