@@ -14,11 +14,10 @@
 // Same MFMA operand layouts, LDS swizzles and direct global->LDS tile loads as
 // fwd_kernel_dma.hpp; 8 wavefronts x 32 query rows; one workgroup barrier per tile.
 //
-// LDS: two stages each for K and V, declared as four separate arrays so that the
-// compiler can prove that the stage the tile loads write is never the one being read
-// (otherwise it waits for the loads before every LDS read).  Iteration j, parity
+// LDS: two stages each for K and V (four arrays; every access names its array because the
+// loop is unrolled by two).  Iteration j, parity
 // r = j % 2: loads K(j+2) -> K[r] and V(j) -> V[r]; reads K(j+1) from K[1-r] and V(j-1)
-// from V[1-r].  The loop is unrolled by two so that every access names its array.
+// from V[1-r].
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -149,36 +148,47 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     }
 
     // ---- tile loads: per tile and matrix each wavefront fills two 1 KiB LDS blocks of 4 key rows;
-    // lane s lands at byte 16*s of its block and fetches the chunk the swizzle wants there.
+    // lane s lands at byte 16*s of its block and fetches the chunk the swizzle wants there.  The
+    // load is written as asm (M0 = LDS block address, SGPR base + 32-bit lane offset): three
+    // instructions per load, and the compiler does not serialise later LDS reads behind it --
+    // the stage being filled is never the one being read, which it cannot see.
     const int ld_row = lane >> 4, ld_pos = lane & 15;
-    int ld_key[2];
-    uint32_t ldk_col[2], ldv_col[2], ldk_off[2], ldv_off[2];
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int key = 4 * (it * NWAVES + wave) + ld_row;
-        ld_key[it] = key;
-        ldk_col[it] = (uint32_t)(ld_pos ^ (key & 15)) * 16u;
-        ldv_col[it] = (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u;
-        ldk_off[it] = (uint32_t)key * kv_stride_b + ldk_col[it];
-        ldv_off[it] = (uint32_t)key * kv_stride_b + ldv_col[it];
+    // byte offsets inside a full tile of this lane's first block; its second block lies 32 keys
+    // further (same swizzle, since 32 is a multiple of both swizzle periods)
+    uint32_t ldk_off0, ldv_off0;
+    {
+        const int key = 4 * wave + ld_row;
+        ldk_off0 = (uint32_t)key * kv_stride_b + (uint32_t)(ld_pos ^ (key & 15)) * 16u;
+        ldv_off0 = (uint32_t)key * kv_stride_b + (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u;
     }
-    auto issue_tile = [&](const unsigned char* base, const uint32_t (&col)[2], const uint32_t (&full_off)[2], int tile,
-                          unsigned char* __restrict__ stage) {
+    const uint32_t block_stride_b = 4u * NWAVES * kv_stride_b;
+    auto dma16 = [](const unsigned char* sbase, uint32_t voff, uint32_t lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(voff), "s"(sbase), "s"(lds_addr)
+                     : "memory");
+    };
+    auto issue_tile = [&](const unsigned char* base, bool is_v, uint32_t full_off0, int tile, unsigned char* stage) {
         if (tile >= n_tiles) return;
         const int key0 = tile * kBN;
-        const int last = sk - 1 - key0;   // rows past the end re-read the last valid row: finite, weight zero
         const unsigned char* tb = base + (int64_t)key0 * kv_stride_b;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)stage + wave * 1024;
+        if (key0 + kBN <= sk) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            uint32_t off = full_off[it];
-            if (last < kBN - 1) off = (uint32_t)min(ld_key[it], last) * kv_stride_b + col[it];
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tb + off),
-                                             (__attribute__((address_space(3))) void*)(stage + (it * NWAVES + wave) * 1024),
-                                             16, 0, 0);
+            for (int it = 0; it < 2; ++it) dma16(tb + it * block_stride_b, full_off0, lds0 + it * NWAVES * 1024);
+        } else {   // rows past the end re-read the last valid row: finite data, weight zero
+            const int last = sk - 1 - key0;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int key = 4 * (it * NWAVES + wave) + ld_row;
+                const uint32_t col = is_v ? (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u
+                                          : (uint32_t)(ld_pos ^ (key & 15)) * 16u;
+                dma16(tb, (uint32_t)min(key, last) * kv_stride_b + col, lds0 + it * NWAVES * 1024);
+            }
         }
     };
-    auto issue_k = [&](int tile, unsigned char* stage) { issue_tile(kbase, ldk_col, ldk_off, tile, stage); };
-    auto issue_v = [&](int tile, unsigned char* stage) { issue_tile(vbase, ldv_col, ldv_off, tile, stage); };
+    auto issue_k = [&](int tile, unsigned char* stage) { issue_tile(kbase, false, ldk_off0, tile, stage); };
+    auto issue_v = [&](int tile, unsigned char* stage) { issue_tile(vbase, true, ldv_off0, tile, stage); };
 
     // ---- LDS operand offsets inside a stage
     uint32_t k_off[8];
