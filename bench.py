@@ -25,8 +25,8 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 matrix peak: 256 CU x 4096 fl
 FLOP_PER_PAIR = 512.0          # per (query, key, head): 2*128 for q.k plus 2*128 for p.v
 # HBM bytes per launch of the dominant kernel (read + written), averaged over the launches of one sweep,
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a device copy of known size
-# (profiles/fwd_kernel_c3_gqa_128k_hbm_traffic.md).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"c3_gqa_128k": 4.464e8}
+# (profiles/fwd_il_kernel_c3_gqa_128k_hbm_traffic.md).  None where not measured.
+MEASURED_TRAFFIC_BYTES = {"c3_gqa_128k": 4.726e8}
 
 
 def parse_args():
@@ -119,7 +119,7 @@ def main():
     achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                "kernel": "pec::fwd_dma_kernel<1, 8>", "launches_per_step": launches,
+                "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)], "launches_per_step": launches,
                 "avg_launch_ms": round(avg_launch_ms, 4), "flop_per_launch_avg": flops / launches}
 
     result = {
@@ -215,7 +215,8 @@ def bench_varlen(args, torch, np, pec, synth, dev):
         "tokens_per_s": round(T / (ms_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": "pec::fwd_dma_kernel<1, 8>"},
+                     "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)]},
     }
     print(json.dumps(result), flush=True)
     return 0

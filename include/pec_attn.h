@@ -136,14 +136,14 @@ enum {
     PEC_VARIANT_W4_Q64 = 0,      /* register-staged tiles: 4 wavefronts x 64 query rows */
     PEC_VARIANT_W8_Q32 = 1,      /* register-staged tiles: 8 wavefronts x 32 query rows */
     PEC_VARIANT_W4_Q64_NOTR = 2, /* as 0 but V operands gathered with scalar LDS reads (slow; cross-check) */
-    PEC_VARIANT_DMA_W8_Q32 = 3,  /* direct global->LDS tiles: 8 wavefronts x 32 query rows (default) */
+    PEC_VARIANT_DMA_W8_Q32 = 3,  /* direct global->LDS tiles: 8 wavefronts x 32 query rows */
     PEC_VARIANT_DMA_W4_Q32 = 4,  /* direct global->LDS tiles: 4 wavefronts x 32 rows, 128-row workgroups */
     PEC_VARIANT_DMA_W4_Q64 = 5,  /* direct global->LDS tiles: 4 wavefronts x 64 query rows */
     PEC_VARIANT_PINGPONG = 6,    /* 8 wavefronts in two groups half a tile apart: one feeds the matrix pipe
                                     while the other does softmax (groups = wavefronts 0-3 / 4-7) */
     PEC_VARIANT_PINGPONG_ADJ = 7,/* same, groups = even / odd wavefronts */
     PEC_VARIANT_INTERLEAVED = 8  /* 8 wavefronts, each software-pipelined: MFMAs of tiles j-1 / j+1 issued
-                                    round-robin with the softmax of tile j */
+                                    round-robin with the softmax of tile j (default) */
 };
 enum {
     PEC_SP_FUSED_MERGE = 0,   /* one pec_attn_chunk_merge launch per ring step (default) */

@@ -20,7 +20,10 @@ PEC_OPT_KERNEL_VARIANT, PEC_OPT_SP_MODE = 0, 1
 PEC_VARIANT_W4_Q64, PEC_VARIANT_W8_Q32, PEC_VARIANT_W4_Q64_NOTR = 0, 1, 2
 PEC_VARIANT_DMA_W8_Q32, PEC_VARIANT_DMA_W4_Q32, PEC_VARIANT_DMA_W4_Q64 = 3, 4, 5
 PEC_VARIANT_PINGPONG, PEC_VARIANT_PINGPONG_ADJ, PEC_VARIANT_INTERLEAVED = 6, 7, 8
-PEC_VARIANT_DEFAULT = PEC_VARIANT_DMA_W8_Q32
+KERNEL_NAMES = {0: "pec::fwd_kernel<2, 4, true>", 1: "pec::fwd_kernel<1, 8, true>", 2: "pec::fwd_kernel<2, 4, false>",
+                3: "pec::fwd_dma_kernel<1, 8>", 4: "pec::fwd_dma_kernel<1, 4>", 5: "pec::fwd_dma_kernel<2, 4>",
+                6: "pec::fwd_pp_kernel<true>", 7: "pec::fwd_pp_kernel<false>", 8: "pec::fwd_il_kernel"}
+PEC_VARIANT_DEFAULT = PEC_VARIANT_INTERLEAVED
 PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
 
 EXPORTS = (

@@ -56,7 +56,7 @@ const Variant kVariants[] = {
 };
 constexpr int N_VARIANTS = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-int g_variant = PEC_VARIANT_DMA_W8_Q32;
+int g_variant = PEC_VARIANT_INTERLEAVED;
 int g_sp_mode = PEC_SP_FUSED_MERGE;
 
 constexpr int64_t kMaxRows = (int64_t)1 << 30;
