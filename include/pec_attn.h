@@ -112,6 +112,25 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
 size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
 
 /*
+ * The same prefill one ring step at a time, for a scheduler that pauses a long prefill between
+ * two kernel operations and resumes it later (section "Preemption of Long-Request Prefill": only
+ * the intermediate data passed between the two operations has to be kept).  Here that data is the
+ * running pair (o_acc fp32 [s_q, Hq, 128], lse_acc fp32 [Hq, s_q]) plus the index of the next step.
+ *   pec_sp_prefill_num_steps: number of KV segments this member visits (>= 0), or a negative status.
+ *   pec_sp_prefill_step: executes visited segment number `step` (0-based, ring order).  Step 0
+ *   initialises (o_acc, lse_acc) and ignores their previous contents; steps must be issued in
+ *   order, each exactly once; anything may run on the GPU, and the state may be copied away and
+ *   back, between two steps.  If out_final is not NULL on the last step the result is written
+ *   there in shape->out_dtype (and o_acc is then left unchanged); lse_acc always ends as the LSE.
+ * Issuing all steps back to back is what pec_sp_prefill does in PEC_SP_FUSED_MERGE mode.
+ */
+int64_t pec_sp_prefill_num_steps(const pec_shape_t* shape, int64_t s_q, int64_t q_off, int64_t s_kv,
+                                 int64_t chunk, int causal);
+int pec_sp_prefill_step(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                        int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk, int causal, int64_t step,
+                        float* o_acc, float* lse_acc, void* out_final, void* stream);
+
+/*
  * Packed batch of independent prompts (batched short prefills colocated with a
  * long request, section "Coordinated Prefill-Decode Colocation and
  * Disaggregation"): sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1 of

@@ -173,6 +173,32 @@ def sp_prefill(q, k, v, *, q_off: int, chunk: int, causal: bool = True, scale: f
     return o, lse
 
 
+def sp_prefill_states(q, k, v, *, q_off: int, chunk: int, causal: bool = True, scale: float | None = None):
+    """The running (O, LSE) pair after each ring step of :func:`sp_prefill`, in order: what a
+    scheduler has to keep when it pauses the prefill between two steps (section "Preemption of
+    Long-Request Prefill").  The last entry is the final result; the list is empty when no
+    segment is visible."""
+    qa, _ = _as_input(q)
+    ka, _ = _as_input(k)
+    va, _ = _as_input(v)
+    sq, hq, d = qa.shape
+    sk = ka.shape[0]
+    n_chunks = max(1, -(-sk // chunk))
+    r = min(q_off // chunk, n_chunks - 1)
+    o = np.zeros((sq, hq, d), dtype=np.float64)
+    lse = np.full((hq, sq), -np.inf, dtype=np.float64)
+    states = []
+    for t in range(n_chunks):
+        c = (r - t) % n_chunks
+        lo, hi = c * chunk, min(sk, (c + 1) * chunk)
+        if hi <= lo or (causal and lo > q_off + sq - 1):
+            continue
+        o_p, lse_p = attention(qa, ka[lo:hi], va[lo:hi], q_off=q_off, kv_off=lo, causal=causal, scale=scale)
+        o, lse = merge(o, lse, o_p, lse_p)
+        states.append((o.copy(), lse.copy()))
+    return states
+
+
 def varlen(q, k, v, cu_seqlens, *, causal: bool = True, scale: float | None = None):
     """Packed batch: sequence b owns rows cu[b]..cu[b+1]-1 and attends only to itself."""
     qa, _ = _as_input(q)

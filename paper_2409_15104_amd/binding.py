@@ -28,7 +28,7 @@ PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
 
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-    "pec_sp_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
+    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
     "pec_get_option", "pec_status_string",
 )
 
@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
         L.pec_sp_prefill.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp, sz, vp]
         L.pec_sp_workspace_bytes.argtypes = [sp, i64]
         L.pec_sp_workspace_bytes.restype = sz
+        L.pec_sp_prefill_num_steps.argtypes = [sp, i64, i64, i64, i64, ci]
+        L.pec_sp_prefill_num_steps.restype = i64
+        L.pec_sp_prefill_step.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, i64, vp, vp, vp, vp]
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
@@ -72,6 +75,7 @@ def lib() -> ctypes.CDLL:
         L.pec_status_string.argtypes = [ci]
         L.pec_status_string.restype = ctypes.c_char_p
         for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
+                     "pec_sp_prefill_step",
                      "pec_attn_varlen", "pec_set_option", "pec_get_option"):
             getattr(L, name).restype = ci
         _lib = L
@@ -200,6 +204,31 @@ def pec_sp_prefill(q, k, v, q_off: int, chunk: int, causal: bool = True, out_dty
                                 int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(),
                                 _stream(stream)))
     return out, lse
+
+
+def pec_sp_prefill_num_steps(q, k, q_off: int, chunk: int, causal: bool = True) -> int:
+    shp = _shape(q, k, torch.bfloat16, 0.0)
+    n = int(lib().pec_sp_prefill_num_steps(ctypes.byref(shp), q.shape[0], int(q_off), k.shape[0], int(chunk),
+                                           int(bool(causal))))
+    if n < 0:
+        raise PecError("pec_sp_prefill_num_steps", n)
+    return n
+
+
+def pec_sp_prefill_step(q, k, v, q_off: int, chunk: int, step: int, o_acc, lse_acc, causal: bool = True,
+                        out_final=None, scale: float = 0.0, stream=None):
+    """Ring step number `step` of the member's prefill, folded into the caller-kept state (o_acc, lse_acc)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    _require(o_acc, torch.float32, "o_acc")
+    _require(lse_acc, torch.float32, "lse_acc")
+    out_dtype = out_final.dtype if out_final is not None else torch.bfloat16
+    shp = _shape(q, k, out_dtype, scale)
+    _check("pec_sp_prefill_step",
+           lib().pec_sp_prefill_step(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), q.shape[0], int(q_off), k.shape[0],
+                                     int(chunk), int(bool(causal)), int(step), _ptr(o_acc), _ptr(lse_acc),
+                                     _ptr(out_final), _stream(stream)))
+    return o_acc, lse_acc
 
 
 def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:

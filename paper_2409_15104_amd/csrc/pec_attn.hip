@@ -126,6 +126,28 @@ int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const voi
     return launch_fwd(p, static_cast<hipStream_t>(stream));
 }
 
+// Ring schedule of one member: step t brings segment (r - t) mod P with r = q_off / chunk (own
+// segment first); under the causal mask segments wholly in the future of every local query are
+// skipped.  Returns the number of visited segments; if `want` is in range, *lo / *len get the
+// want-th visited segment.
+int64_t ring_visit(int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk, int causal, int64_t want, int64_t* lo,
+                   int64_t* len) {
+    if (s_kv <= 0) return 0;
+    const int64_t n_chunks = (s_kv + chunk - 1) / chunk;
+    const int64_t r = std::min(q_off / chunk, n_chunks - 1);
+    int64_t visited = 0;
+    for (int64_t t = 0; t < n_chunks; ++t) {
+        const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
+        if (causal && c * chunk > q_off + s_q - 1) continue;
+        if (visited == want) {
+            *lo = c * chunk;
+            *len = std::min(chunk, s_kv - c * chunk);
+        }
+        ++visited;
+    }
+    return visited;
+}
+
 int grid_for(int64_t n_groups) { return (int)std::min<int64_t>((n_groups + 255) / 256, 256 * 32); }
 
 }  // namespace
@@ -206,76 +228,106 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
         return chunk_impl(shape, q, k, v, s_q, s_kv, q_off, 0, causal, out, out_f32, lse, nullptr, nullptr, nullptr, s_q,
                           stream);
 
-    // ring order: step t brings segment (r - t) mod P, the member's own segment first
-    const int64_t n_chunks = (s_kv + chunk - 1) / chunk;
-    const int64_t r = std::min(q_off / chunk, n_chunks - 1);
-    int64_t visit_count = 0;
-    for (int64_t t = 0; t < n_chunks; ++t) {
-        const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
-        if (causal && c * chunk > q_off + s_q - 1) continue;
-        ++visit_count;
-    }
-    if (visit_count == 0)  // nothing visible at all: out = 0, lse = -inf
+    int64_t lo = 0, len = 0;
+    const int64_t n_steps = ring_visit(s_q, q_off, s_kv, chunk, causal, 0, &lo, &len);
+    if (n_steps == 0)  // nothing visible at all: out = 0, lse = -inf
         return chunk_impl(shape, q, k, v, s_q, 0, q_off, 0, causal, out, out_f32, lse, nullptr, nullptr, nullptr, s_q,
                           stream);
-    if (visit_count == 1) {
-        for (int64_t t = 0; t < n_chunks; ++t) {
-            const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
-            if (causal && c * chunk > q_off + s_q - 1) continue;
-            const int64_t lo = c * chunk, len = std::min(chunk, s_kv - lo);
-            return chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, out, out_f32,
-                              lse, nullptr, nullptr, nullptr, s_q, stream);
-        }
-    }
+    if (n_steps == 1)
+        return chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, out, out_f32, lse,
+                          nullptr, nullptr, nullptr, s_q, stream);
 
     if (!workspace || workspace_bytes < pec_sp_workspace_bytes(shape, s_q)) return PEC_ERR_WORKSPACE;
     const size_t o_bytes = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
     float* o_acc = static_cast<float*>(workspace);
+
+    if (g_sp_mode == PEC_SP_FUSED_MERGE) {
+        for (int64_t t = 0; t < n_steps; ++t) {
+            const int rc = pec_sp_prefill_step(shape, q, k, v, s_q, q_off, s_kv, chunk, causal, t, o_acc, lse,
+                                               t == n_steps - 1 ? out : nullptr, stream);
+            if (rc != PEC_OK) return rc;
+        }
+        return PEC_OK;
+    }
+
+    // PEC_SP_SEPARATE_MERGE: fp32 partial of every step through HBM, stand-alone merge kernel
     float* o_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + o_bytes);
     float* lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * o_bytes);
     pec_shape_t part_shape = *shape;
     part_shape.out_dtype = PEC_F32;
-
-    int64_t visited = 0;
-    for (int64_t t = 0; t < n_chunks; ++t) {
-        const int64_t c = ((r - t) % n_chunks + n_chunks) % n_chunks;
-        const int64_t lo = c * chunk, len = std::min(chunk, s_kv - lo);
-        if (causal && lo > q_off + s_q - 1) continue;  // wholly in the future of every local query
-        const bool first = visited == 0, last = visited == visit_count - 1;
+    for (int64_t t = 0; t < n_steps; ++t) {
+        ring_visit(s_q, q_off, s_kv, chunk, causal, t, &lo, &len);
         int rc;
-        if (g_sp_mode == PEC_SP_FUSED_MERGE) {
-            if (first)  // starts the running state: plain chunk call writing fp32 O into o_acc
-                rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_acc,
-                                1, lse, nullptr, nullptr, nullptr, s_q, stream);
-            else if (!last)
-                rc = chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, nullptr,
-                                out_f32, lse, o_acc, lse, o_acc, s_q, stream);
-            else  // last step: the merged result goes straight to `out`
-                rc = chunk_impl(shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, out, out_f32,
-                                lse, o_acc, lse, nullptr, s_q, stream);
+        if (t == 0) {
+            rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_acc, 1,
+                            lse, nullptr, nullptr, nullptr, s_q, stream);
         } else {
-            if (first) {
-                rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_acc,
-                                1, lse, nullptr, nullptr, nullptr, s_q, stream);
-            } else {
-                rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_part,
-                                1, lse_part, nullptr, nullptr, nullptr, s_q, stream);
-                if (rc == PEC_OK) rc = pec_attn_merge(&part_shape, o_acc, lse, o_part, lse_part, s_q, stream);
-            }
-            if (rc == PEC_OK && last) {
-                if (out_f32) {
-                    if (hipMemcpyAsync(out, o_acc, o_bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)) !=
-                        hipSuccess)
-                        rc = PEC_ERR_HIP;
-                } else {
-                    rc = pec_finalize(shape, o_acc, out, s_q, stream);
-                }
-            }
+            rc = chunk_impl(&part_shape, q, kp + lo * kv_row, vp + lo * kv_row, s_q, len, q_off, lo, causal, o_part, 1,
+                            lse_part, nullptr, nullptr, nullptr, s_q, stream);
+            if (rc == PEC_OK) rc = pec_attn_merge(&part_shape, o_acc, lse, o_part, lse_part, s_q, stream);
         }
         if (rc != PEC_OK) return rc;
-        ++visited;
     }
-    return PEC_OK;
+    if (out_f32) {
+        if (hipMemcpyAsync(out, o_acc, o_bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)) != hipSuccess)
+            return PEC_ERR_HIP;
+        return PEC_OK;
+    }
+    return pec_finalize(shape, o_acc, out, s_q, stream);
+}
+
+int64_t pec_sp_prefill_num_steps(const pec_shape_t* shape, int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk,
+                                 int causal) {
+    if (int rc = check_shape(shape, nullptr)) return rc;
+    if (s_q < 0 || s_kv < 0 || chunk <= 0 || q_off < 0) return PEC_ERR_INVALID_ARGUMENT;
+    int64_t lo, len;
+    return ring_visit(s_q, q_off, s_kv, chunk, causal, -1, &lo, &len);
+}
+
+int pec_sp_prefill_step(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t s_q,
+                        int64_t q_off, int64_t s_kv, int64_t chunk, int causal, int64_t step, float* o_acc,
+                        float* lse_acc, void* out_final, void* stream) {
+    if (int rc = check_shape(shape, nullptr)) return rc;
+    if (s_q < 0 || s_kv < 0 || chunk <= 0 || q_off < 0 || step < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (s_q > kMaxRows || s_kv > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (s_q == 0) return PEC_OK;
+    if (!o_acc || !lse_acc) return PEC_ERR_INVALID_ARGUMENT;
+    int64_t lo = 0, len = 0;
+    const int64_t n_steps = ring_visit(s_q, q_off, s_kv, chunk, causal, step, &lo, &len);
+    const int out_f32 = shape->out_dtype == PEC_F32;
+    const int64_t kv_row = (int64_t)shape->n_kv_heads * kHeadDim;
+    const __bf16* kp = static_cast<const __bf16*>(k) + lo * kv_row;
+    const __bf16* vp = static_cast<const __bf16*>(v) + lo * kv_row;
+    if (n_steps == 0 && step == 0) {  // nothing visible: the state (and the result) is the empty pair
+        int rc = chunk_impl(shape, q, k, v, s_q, 0, q_off, 0, causal, o_acc, 1, lse_acc, nullptr, nullptr, nullptr, s_q,
+                            stream);
+        if (rc == PEC_OK && out_final)
+            rc = chunk_impl(shape, q, k, v, s_q, 0, q_off, 0, causal, out_final, out_f32, lse_acc, nullptr, nullptr,
+                            nullptr, s_q, stream);
+        return rc;
+    }
+    if (step >= n_steps) return PEC_ERR_INVALID_ARGUMENT;
+    const bool last = step == n_steps - 1;
+    if (step == 0) {  // starts the running state; a one-step prefill may also emit the final output
+        int rc = chunk_impl(shape, q, kp, vp, s_q, len, q_off, lo, causal, o_acc, 1, lse_acc, nullptr, nullptr, nullptr,
+                            s_q, stream);
+        if (rc == PEC_OK && last && out_final) {
+            if (out_f32) {
+                const size_t o_bytes = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
+                if (hipMemcpyAsync(out_final, o_acc, o_bytes, hipMemcpyDeviceToDevice,
+                                   static_cast<hipStream_t>(stream)) != hipSuccess)
+                    rc = PEC_ERR_HIP;
+            } else {
+                rc = pec_finalize(shape, o_acc, out_final, s_q, stream);
+            }
+        }
+        return rc;
+    }
+    // later steps fold the segment into the running state; on the last one the merged result can go
+    // straight to out_final, and the fp32 state, no longer needed, is then left as it was
+    float* acc_out = (last && out_final) ? nullptr : o_acc;
+    return chunk_impl(shape, q, kp, vp, s_q, len, q_off, lo, causal, out_final, out_f32, lse_acc, o_acc, lse_acc, acc_out,
+                      s_q, stream);
 }
 
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens) {

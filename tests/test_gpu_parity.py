@@ -320,3 +320,48 @@ def test_full_size_gqa_512k_last_member_sampled_rows():
     out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
     rows = synth.sample_rows(w.seed, w.chunk, boundaries=(), n_random=6, edge=1)
     _sampled_check(q, k, v, out, lse, q_off, rows, heads=3, what="c5 last member")
+
+
+def test_resumable_prefill_states_match_oracle_and_survive_preemption():
+    """pec_sp_prefill_step: the running (O, LSE) after every ring step against the oracle's, and a
+    prefill that is paused after every step -- other work runs on the GPU, the state is swapped
+    out to the host and back -- ends bit-identical to the uninterrupted pec_sp_prefill."""
+    s, hq, hkv, chunk = 1500, 8, 2, 256                       # 6 segments, the last one short
+    q_all, k, v = synth.qkv(23, s, s, hq, hkv)
+    qd_all, kd, vd = gpu(q_all, k, v)
+    lengths = [300, 64, 700]
+    cu = torch.from_numpy(synth.cu_seqlens_of(lengths)).to(DEV)
+    qs, ks, vs = gpu(*synth.qkv(24, sum(lengths), sum(lengths), hq, hkv))
+    for r in (5, 3, 0):
+        lo, hi = r * chunk, min(s, (r + 1) * chunk)
+        qd = qd_all[lo:hi].contiguous()
+        n = pec.pec_sp_prefill_num_steps(qd, kd, lo, chunk)
+        assert n == r + 1
+        states = oracle.sp_prefill_states(q_all[lo:hi], k, v, q_off=lo, chunk=chunk, causal=True)
+        ref_out, ref_lse = pec.pec_sp_prefill(qd, kd, vd, lo, chunk, True)
+        o_acc = torch.full((hi - lo, hq, 128), float("nan"), dtype=torch.float32, device=DEV)   # step 0 must not read it
+        l_acc = torch.full((hq, hi - lo), float("nan"), dtype=torch.float32, device=DEV)
+        out = torch.empty((hi - lo, hq, 128), dtype=torch.bfloat16, device=DEV)
+        for t in range(n):
+            pec.pec_sp_prefill_step(qd, kd, vd, lo, chunk, t, o_acc, l_acc, True, out_final=out if t == n - 1 else None)
+            if t < n - 1:
+                assert_close(o_acc, l_acc, states[t][0], states[t][1], "member %d state after step %d" % (r, t))
+                # preempted: a batch of short prompts runs, the state leaves the GPU and comes back
+                pec.pec_attn_varlen(qs, ks, vs, cu, max(lengths), True)
+                o_host, l_host = o_acc.cpu(), l_acc.cpu()
+                o_acc.fill_(float("nan"))
+                l_acc.fill_(float("nan"))
+                o_acc.copy_(o_host)
+                l_acc.copy_(l_host)
+        assert_close(out, l_acc, states[-1][0], states[-1][1], "member %d final" % r)
+        assert torch.equal(out, ref_out) and torch.equal(l_acc, ref_lse)
+    # a member that sees nothing (its segment lies before kv position 0 is impossible; use s_kv = 0)
+    qd = qd_all[:100].contiguous()
+    assert pec.pec_sp_prefill_num_steps(qd, kd[:0], 0, chunk) == 0
+    o_acc = torch.full((100, hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    l_acc = torch.full((hq, 100), float("nan"), dtype=torch.float32, device=DEV)
+    out = torch.empty((100, hq, 128), dtype=torch.bfloat16, device=DEV)
+    pec.pec_sp_prefill_step(qd, kd[:0], vd[:0], 0, chunk, 0, o_acc, l_acc, True, out_final=out)
+    assert torch.all(o_acc == 0) and torch.all(out == 0) and torch.all(l_acc == -math.inf)
+    with pytest.raises(pec.PecError):
+        pec.pec_sp_prefill_step(qd, kd, vd, 0, chunk, 7, o_acc, l_acc, True)

@@ -253,6 +253,21 @@ def test_ring_schedule_and_sp_prefill():
     np.testing.assert_allclose(lse, l_nc, rtol=0, atol=1e-12)
 
 
+def test_paused_prefill_state_is_attention_over_the_segments_seen_so_far():
+    s, hq, hkv, d, chunk = 47, 4, 2, 8, 10
+    q_all, k, v = _rand((s, hq, d), 53), _rand((s, hkv, d), 54), _rand((s, hkv, d), 55)
+    for r in (0, 2, 4):
+        lo, hi = r * chunk, min(s, (r + 1) * chunk)
+        states = oracle.sp_prefill_states(q_all[lo:hi], k, v, q_off=lo, chunk=chunk, causal=True)
+        assert len(states) == r + 1
+        for t, (o_t, l_t) in enumerate(states):          # after t+1 steps: segments r, r-1, ..., r-t
+            klo = (r - t) * chunk
+            o_ref, l_ref = oracle.attention(q_all[lo:hi], k[klo:hi], v[klo:hi], q_off=lo, kv_off=klo, causal=True)
+            np.testing.assert_allclose(o_t, o_ref, rtol=0, atol=1e-12)
+            np.testing.assert_allclose(l_t, l_ref, rtol=0, atol=1e-12)
+    assert oracle.sp_prefill_states(q_all[:5], k[:0], v[:0], q_off=0, chunk=chunk) == []
+
+
 def test_varlen_is_per_sequence_dense_and_leak_free():
     lengths = [5, 0, 1, 9, 3]
     cu = synth.cu_seqlens_of(lengths)
