@@ -6,7 +6,7 @@ segment r = 0..P-1 runs pec_sp_prefill over the KV segments it can see, in ring
 order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen|decode_512k]
                   [--sp-mode fused|separate|single] [--variant N] [--no-cpu-baseline]
 """
 from __future__ import annotations
@@ -78,6 +78,8 @@ def main():
 
     if args.workload == "c4_varlen":
         return bench_varlen(args, torch, np, pec, synth, dev)
+    if args.workload.startswith("decode"):
+        return bench_decode(args, torch, np, pec, synth, dev)
 
     w = synth.WORKLOADS[args.workload]
     S, C, Hq, Hkv = w.seq, w.chunk, w.n_q_heads, w.n_kv_heads
@@ -217,6 +219,47 @@ def bench_varlen(args, torch, np, pec, synth, dev):
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)]},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_decode(args, torch, np, pec, synth, dev):
+    """Long-request decode step: one new token against a 524,288-token KV-cache shard (64 q / 8 kv heads).
+    HBM-bound: K and V are read once."""
+    Hq, Hkv, sk = 64, 8, 524288
+    q, k, v = synth.qkv(1005, 1, sk, Hq, Hkv, device=dev)
+    n_splits = 64
+    out = torch.empty((1, Hq, 128), dtype=torch.float32, device=dev)
+    lse = torch.empty((Hq,), dtype=torch.float32, device=dev)
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device=dev)
+    algo_bytes = 2.0 * sk * Hkv * 128 * 2 + 2 * Hq * 128 * 2 + Hq * 4      # K + V once, q, out, lse
+
+    def step():
+        pec.pec_decode_splitkv(q, k, v, n_splits=n_splits, out=out, lse=lse, workspace=ws)
+
+    for _ in range(max(args.warmup, 3)):
+        step()
+    torch.cuda.synchronize()
+    steps = max(args.steps, 20)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = ev0.elapsed_time(ev1) / steps
+    gbs = algo_bytes / (ev_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode attention step over a 512K-token KV shard", "value": round(1e3 / ms_step, 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 3), "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "decode_512k: 1 query token, 64 q / 8 kv heads, KV shard of 524288 tokens, %d key splits"
+                               % n_splits},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+                     "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::fwd_il_kernel (split-KV) + combine"},
     }
     print(json.dumps(result), flush=True)
     return 0

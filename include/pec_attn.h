@@ -146,6 +146,23 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
                     int causal, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens);
 
+/*
+ * Decode attention of a long request kept on its prefill GPUs while short prefills share them
+ * (section "Coordinated Prefill-Decode Colocation and Disaggregation"): ONE new token, q [1, Hq, 128],
+ * against this GPU's shard of the KV cache, k/v [sk, Hkv, 128]; every key is visible.  The shard is
+ * cut into n_splits key ranges processed by separate workgroups (0 = pick a default), the partial
+ * (O, LSE) pairs are combined exactly by log-sum-exp.  out [1, Hq, 128] in shape->out_dtype and
+ * lse [Hq] form a partial pair over this shard: results of several shards / GPUs (the paper's
+ * example merges the outputs of two GPUs) combine with pec_attn_merge (use out_dtype PEC_F32).
+ * sk == 0 gives out = 0, lse = -inf.  workspace: pec_decode_workspace_bytes() bytes.
+ * HBM-bound: K and V are read once, 2 * sk * Hkv * 128 * 2 bytes.
+ */
+int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
+                       int32_t n_splits, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                       void* stream);
+int32_t pec_decode_default_splits(int64_t sk);
+size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits);
+
 /* Tuning knobs; process-wide, not thread-safe against concurrent calls. */
 enum {
     PEC_OPT_KERNEL_VARIANT = 0, /* see PEC_VARIANT_* */

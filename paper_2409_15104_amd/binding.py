@@ -28,7 +28,8 @@ PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
 
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
+    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_decode_default_splits",
+    "pec_decode_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
     "pec_get_option", "pec_status_string",
 )
 
@@ -67,6 +68,11 @@ def lib() -> ctypes.CDLL:
         L.pec_sp_prefill_num_steps.argtypes = [sp, i64, i64, i64, i64, ci]
         L.pec_sp_prefill_num_steps.restype = i64
         L.pec_sp_prefill_step.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, i64, vp, vp, vp, vp]
+        L.pec_decode_splitkv.argtypes = [sp, vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+        L.pec_decode_default_splits.argtypes = [i64]
+        L.pec_decode_default_splits.restype = i32
+        L.pec_decode_workspace_bytes.argtypes = [sp, i32]
+        L.pec_decode_workspace_bytes.restype = sz
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
@@ -75,7 +81,7 @@ def lib() -> ctypes.CDLL:
         L.pec_status_string.argtypes = [ci]
         L.pec_status_string.restype = ctypes.c_char_p
         for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-                     "pec_sp_prefill_step",
+                     "pec_sp_prefill_step", "pec_decode_splitkv",
                      "pec_attn_varlen", "pec_set_option", "pec_get_option"):
             getattr(L, name).restype = ci
         _lib = L
@@ -229,6 +235,31 @@ def pec_sp_prefill_step(q, k, v, q_off: int, chunk: int, step: int, o_acc, lse_a
                                      int(chunk), int(bool(causal)), int(step), _ptr(o_acc), _ptr(lse_acc),
                                      _ptr(out_final), _stream(stream)))
     return o_acc, lse_acc
+
+
+def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scale: float = 0.0, out=None, lse=None,
+                       workspace=None, stream=None):
+    """One new token q [1,Hq,128] against a KV-cache shard k/v [sk,Hkv,128] -> (out [1,Hq,128], lse [Hq])."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    if q.shape[0] != 1:
+        raise ValueError("pec_decode_splitkv takes exactly one query token")
+    hq = q.shape[1]
+    sk = k.shape[0]
+    shp = _shape(q, k, out_dtype, scale)
+    if n_splits == 0:
+        n_splits = int(lib().pec_decode_default_splits(sk))
+    if out is None:
+        out = torch.empty((1, hq, 128), dtype=out_dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((hq,), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, int(lib().pec_decode_workspace_bytes(ctypes.byref(shp), n_splits))),
+                                dtype=torch.uint8, device=q.device)
+    _check("pec_decode_splitkv",
+           lib().pec_decode_splitkv(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), sk, int(n_splits), _ptr(out),
+                                    _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out, lse
 
 
 def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:

@@ -59,6 +59,34 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
         reinterpret_cast<bf16x4*>(dst)[g] = __builtin_convertvector(reinterpret_cast<const f32x4*>(src)[g], bf16x4);
 }
 
+// Combines the partial results of a split-KV decode: for every head, L = ln sum_s exp(lse_s) and
+// O = sum_s O_s exp(lse_s - L) over the n_splits disjoint key ranges (the two-set merge applied to
+// all ranges at once).  One workgroup of 128 threads per head; partials are fp32
+// [n_splits][n_heads][128] and [n_splits][n_heads].
+template <bool OUT_F32>
+__global__ __launch_bounds__(128) void combine_splits_kernel(const float* __restrict__ o_part,
+                                                             const float* __restrict__ lse_part, int n_splits,
+                                                             int n_heads, void* __restrict__ out,
+                                                             float* __restrict__ lse) {
+    const int h = blockIdx.x, d = threadIdx.x;
+    float mx = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, lse_part[(int64_t)s * n_heads + h]);
+    float den = 0.f, acc = 0.f;
+    if (mx != -INFINITY) {
+        for (int s = 0; s < n_splits; ++s) {
+            const float w = expf(lse_part[(int64_t)s * n_heads + h] - mx);
+            den += w;
+            acc += w * o_part[((int64_t)s * n_heads + h) * kHeadDim + d];
+        }
+        acc /= den;
+    }
+    if constexpr (OUT_F32)
+        reinterpret_cast<float*>(out)[(int64_t)h * kHeadDim + d] = acc;
+    else
+        reinterpret_cast<__bf16*>(out)[(int64_t)h * kHeadDim + d] = (__bf16)acc;
+    if (d == 0) lse[h] = mx != -INFINITY ? mx + logf(den) : -INFINITY;
+}
+
 // Work list for a packed batch: one item per (sequence, query tile), ordered by
 // descending query-tile index so the longest causal rows start first.  Single
 // workgroup; `bucket` and `cursor` are int32[max_qtiles] scratch.

@@ -70,6 +70,13 @@ struct FwdParams {
     const WorkItem* work;
     const int32_t* n_work;  // number of valid work items
     int32_t total_tokens;   // rows of the packed arrays (bounds every index taken from cu_seqlens)
+    // split-KV mode (kv_split_len > 0; fwd_il_kernel only): work item = key range
+    // [item * kv_split_len, ...), partial results go to out / lse + item * split_*_stride
+    int32_t kv_split_len;
+    int64_t split_out_stride, split_lse_stride;   // elements
+    // element strides of q / out / acc between rows and between heads (0 = the packed
+    // [tokens, n_q_heads, 128] layout; fwd_il_kernel only)
+    int64_t q_row_stride, q_head_stride;
 };
 
 __device__ __forceinline__ uint32_t k_lds_off(int key, int chunk16) {

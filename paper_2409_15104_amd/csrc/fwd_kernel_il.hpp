@@ -80,6 +80,14 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         qt = p.causal ? (p.n_items - 1 - item) : item;  // longest rows first
         q_tok0 = kv_tok0 = 0;
     }
+    int64_t split_out = 0, split_lse = 0;
+    if (p.kv_split_len > 0) {   // the work item is a key range; all of it is visible (decode)
+        qt = 0;
+        kv_tok0 = (int64_t)item * p.kv_split_len;
+        sk = (int)max((int64_t)0, min((int64_t)p.kv_split_len, (int64_t)p.sk - kv_tok0));
+        split_out = item * p.split_out_stride;
+        split_lse = item * p.split_lse_stride;
+    }
     const int causal = p.causal;
     const int row0 = qt * BM;
     const int rw0 = row0 + wave * 32;
@@ -99,8 +107,10 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     }
     n_full = min(n_full, n_tiles);
     n_act = max(n_act, n_full);
+    if (rw0 >= sq) n_full = n_act = 0;   // a wavefront without a valid row only helps loading tiles
 
-    const int64_t q_stride = (int64_t)p.n_q_heads * kHeadDim;
+    const int64_t q_stride = p.q_row_stride ? p.q_row_stride : (int64_t)p.n_q_heads * kHeadDim;
+    const int64_t q_head_off = (int64_t)head * (p.q_head_stride ? p.q_head_stride : kHeadDim);
     const uint32_t kv_stride_b = (uint32_t)p.n_kv_heads * kHeadDim * 2;   // bytes per token
     const unsigned char* kbase =
         reinterpret_cast<const unsigned char*>(p.k) + (kv_tok0 * p.n_kv_heads + kvh) * (int64_t)(kHeadDim * 2);
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     bf16x8 qf[8];
     {
         const int row = rw0 + l32;
-        const __bf16* qrow = p.q + (q_tok0 + row) * q_stride + (int64_t)head * kHeadDim + 8 * hl;
+        const __bf16* qrow = p.q + (q_tok0 + row) * q_stride + q_head_off + 8 * hl;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             u32x4 raw = {0u, 0u, 0u, 0u};
@@ -134,7 +144,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
             if (lin != -INFINITY) {
                 m_run = lin * kLog2e;
                 l_run = hl == 0 ? 1.f : 0.f;
-                const float* arow = p.acc_in + (q_tok0 + row) * q_stride + (int64_t)head * kHeadDim + 4 * hl;
+                const float* arow = p.acc_in + (q_tok0 + row) * q_stride + q_head_off + 4 * hl;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -437,8 +447,8 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         if (row < sq) {
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-            if (hl == 0) p.lse[(int64_t)head * p.lse_stride + q_tok0 + row] = lse;
-            const int64_t obase = (q_tok0 + row) * q_stride + (int64_t)head * kHeadDim + 4 * hl;
+            if (hl == 0) p.lse[split_lse + (int64_t)head * p.lse_stride + q_tok0 + row] = lse;
+            const int64_t obase = split_out + (q_tok0 + row) * q_stride + q_head_off + 4 * hl;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll

@@ -330,6 +330,71 @@ int pec_sp_prefill_step(const pec_shape_t* shape, const void* q, const void* k, 
                       s_q, stream);
 }
 
+int32_t pec_decode_default_splits(int64_t sk) {
+    if (sk <= 0) return 1;
+    // at least 16 tiles of 64 keys per split, at most 64 splits (x n_kv_heads workgroups)
+    return (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, sk / 1024));
+}
+
+size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits) {
+    if (!shape || shape->n_q_heads <= 0 || n_splits <= 0) return 0;
+    return (size_t)n_splits * shape->n_q_heads * (kHeadDim + 1) * sizeof(float);
+}
+
+int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
+                       int32_t n_splits, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (sk < 0 || n_splits < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (sk > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (!q || !out || !lse || (sk > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace))
+        return PEC_ERR_MISALIGNED;
+    if (n_splits == 0) n_splits = pec_decode_default_splits(sk);
+    const int g = shape->n_q_heads / shape->n_kv_heads;
+    if (g > 256) return PEC_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < pec_decode_workspace_bytes(shape, n_splits)) return PEC_ERR_WORKSPACE;
+    float* o_part = static_cast<float*>(workspace);
+    float* lse_part = o_part + (size_t)n_splits * shape->n_q_heads * kHeadDim;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // The g query heads of one KV head become the g rows of one query tile: row stride 128, "head"
+    // (= KV head) stride g*128; the work items are the key ranges.
+    FwdParams p{};
+    p.q = static_cast<const __bf16*>(q);
+    p.k = static_cast<const __bf16*>(k);
+    p.v = static_cast<const __bf16*>(v);
+    p.out = o_part;
+    p.lse = lse_part;
+    p.lse_stride = g;
+    p.sq = g;
+    p.sk = (int32_t)sk;
+    p.delta = (int32_t)sk;
+    p.causal = 0;
+    p.n_q_heads = shape->n_kv_heads;
+    p.n_kv_heads = shape->n_kv_heads;
+    p.group = 1;
+    p.n_items = n_splits;
+    p.out_f32 = 1;
+    p.scale_log2 = scale * kLog2e;
+    const int64_t split_len = ((sk + n_splits - 1) / n_splits + kBN - 1) / kBN * kBN;   // whole tiles
+    p.kv_split_len = (int32_t)std::max<int64_t>(split_len, kBN);
+    p.split_out_stride = (int64_t)shape->n_q_heads * kHeadDim;
+    p.split_lse_stride = shape->n_q_heads;
+    p.q_row_stride = kHeadDim;
+    p.q_head_stride = (int64_t)g * kHeadDim;
+    const int64_t total = (int64_t)n_splits * shape->n_kv_heads;
+    launch_il(p, (unsigned)(((total + 7) / 8) * 8), st);
+    if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+    if (shape->out_dtype == PEC_F32)
+        hipLaunchKernelGGL((combine_splits_kernel<true>), dim3(shape->n_q_heads), dim3(128), 0, st, o_part, lse_part,
+                           (int)n_splits, (int)shape->n_q_heads, out, lse);
+    else
+        hipLaunchKernelGGL((combine_splits_kernel<false>), dim3(shape->n_q_heads), dim3(128), 0, st, o_part, lse_part,
+                           (int)n_splits, (int)shape->n_q_heads, out, lse);
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens) {
     if (batch < 0 || total_tokens < 0) return 0;
     const size_t cap = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;

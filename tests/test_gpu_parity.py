@@ -365,3 +365,31 @@ def test_resumable_prefill_states_match_oracle_and_survive_preemption():
     assert torch.all(o_acc == 0) and torch.all(out == 0) and torch.all(l_acc == -math.inf)
     with pytest.raises(pec.PecError):
         pec.pec_sp_prefill_step(qd, kd, vd, 0, chunk, 7, o_acc, l_acc, True)
+
+
+@pytest.mark.parametrize("sk,hq,hkv,n_splits", [(1, 8, 8, 0), (63, 8, 2, 1), (64, 4, 4, 3), (700, 32, 8, 0),
+                                                (5000, 64, 8, 7), (70000, 32, 8, 0), (0, 8, 2, 0)])
+def test_decode_splitkv_matches_oracle(sk, hq, hkv, n_splits):
+    """One new token against a KV-cache shard (long-request decode colocated with short prefills)."""
+    q, k, v = synth.qkv(31 + sk, 1, sk, hq, hkv)
+    o_ref, l_ref = oracle.attention(q, k, v, causal=False)
+    for out_dtype in (torch.float32, torch.bfloat16):
+        out, lse = pec.pec_decode_splitkv(*gpu(q, k, v), n_splits=n_splits, out_dtype=out_dtype)
+        assert_close(out, lse.reshape(hq, 1), o_ref, l_ref, "decode sk=%d %s" % (sk, out_dtype))
+
+
+def test_decode_over_two_shards_merges_like_the_two_gpu_example():
+    """The long request's KV cache lives on two GPUs; each computes its partial, the partials are
+    merged (here: both shards on the one GPU, merged with pec_attn_merge)."""
+    sk, hq, hkv = 9000, 32, 8
+    q, k, v = synth.qkv(37, 1, sk, hq, hkv)
+    o_ref, l_ref = oracle.attention(q, k, v, causal=False)
+    qd, kd, vd = gpu(q, k, v)
+    cut = 5123
+    o1, l1 = pec.pec_decode_splitkv(qd, kd[:cut], vd[:cut], out_dtype=torch.float32)
+    o2, l2 = pec.pec_decode_splitkv(qd, kd[cut:], vd[cut:], out_dtype=torch.float32)
+    o, lse = pec.pec_attn_merge(o1, l1.reshape(hq, 1).contiguous(), o2, l2.reshape(hq, 1).contiguous())
+    assert_close(o, lse, o_ref, l_ref, "two-shard decode")
+    # all keys identical, Q = 0: every key weighs 1/sk, LSE = ln sk exactly
+    _, l0 = pec.pec_decode_splitkv(torch.zeros_like(qd), kd, vd)
+    assert np.all(np.rint(np.exp(l0.cpu().numpy().astype(np.float64))) == sk)
