@@ -229,7 +229,7 @@ def bench_decode(args, torch, np, pec, synth, dev):
     HBM-bound: K and V are read once."""
     Hq, Hkv, sk = 64, 8, 524288
     q, k, v = synth.qkv(1005, 1, sk, Hq, Hkv, device=dev)
-    n_splits = 64
+    n_splits = 256 // Hkv        # the library's default for this shape: one workgroup per compute unit
     out = torch.empty((1, Hq, 128), dtype=torch.float32, device=dev)
     lse = torch.empty((Hq,), dtype=torch.float32, device=dev)
     ws = torch.empty(1 << 22, dtype=torch.uint8, device=dev)

@@ -160,7 +160,7 @@ size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens);
 int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
                        int32_t n_splits, void* out, float* lse, void* workspace, size_t workspace_bytes,
                        void* stream);
-int32_t pec_decode_default_splits(int64_t sk);
+int32_t pec_decode_default_splits(const pec_shape_t* shape, int64_t sk);
 size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits);
 
 /* Tuning knobs; process-wide, not thread-safe against concurrent calls. */

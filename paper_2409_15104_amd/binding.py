@@ -69,7 +69,7 @@ def lib() -> ctypes.CDLL:
         L.pec_sp_prefill_num_steps.restype = i64
         L.pec_sp_prefill_step.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, i64, vp, vp, vp, vp]
         L.pec_decode_splitkv.argtypes = [sp, vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
-        L.pec_decode_default_splits.argtypes = [i64]
+        L.pec_decode_default_splits.argtypes = [sp, i64]
         L.pec_decode_default_splits.restype = i32
         L.pec_decode_workspace_bytes.argtypes = [sp, i32]
         L.pec_decode_workspace_bytes.restype = sz
@@ -248,7 +248,7 @@ def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scal
     sk = k.shape[0]
     shp = _shape(q, k, out_dtype, scale)
     if n_splits == 0:
-        n_splits = int(lib().pec_decode_default_splits(sk))
+        n_splits = int(lib().pec_decode_default_splits(ctypes.byref(shp), sk))
     if out is None:
         out = torch.empty((1, hq, 128), dtype=out_dtype, device=q.device)
     if lse is None:

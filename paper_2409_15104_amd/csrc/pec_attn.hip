@@ -330,10 +330,12 @@ int pec_sp_prefill_step(const pec_shape_t* shape, const void* q, const void* k, 
                       s_q, stream);
 }
 
-int32_t pec_decode_default_splits(int64_t sk) {
-    if (sk <= 0) return 1;
-    // at least 16 tiles of 64 keys per split, at most 64 splits (x n_kv_heads workgroups)
-    return (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, sk / 1024));
+int32_t pec_decode_default_splits(const pec_shape_t* shape, int64_t sk) {
+    if (!shape || shape->n_kv_heads <= 0 || sk <= 0) return 1;
+    // one workgroup per compute unit measured best (256 CUs / n_kv_heads key ranges), with at
+    // least 16 tiles of 64 keys per range
+    const int64_t per_cu = std::max<int64_t>(1, 256 / shape->n_kv_heads);
+    return (int32_t)std::max<int64_t>(1, std::min<int64_t>(per_cu, sk / 1024));
 }
 
 size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits) {
@@ -350,7 +352,7 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
     if (!q || !out || !lse || (sk > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace))
         return PEC_ERR_MISALIGNED;
-    if (n_splits == 0) n_splits = pec_decode_default_splits(sk);
+    if (n_splits == 0) n_splits = pec_decode_default_splits(shape, sk);
     const int g = shape->n_q_heads / shape->n_kv_heads;
     if (g > 256) return PEC_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < pec_decode_workspace_bytes(shape, n_splits)) return PEC_ERR_WORKSPACE;
