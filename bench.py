@@ -6,7 +6,7 @@ segment r = 0..P-1 runs pec_sp_prefill over the KV segments it can see, in ring
 order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen|decode_512k]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen|decode_512k|ulysses_layout]
                   [--sp-mode fused|separate|single] [--variant N] [--no-cpu-baseline]
 """
 from __future__ import annotations
@@ -80,6 +80,8 @@ def main():
         return bench_varlen(args, torch, np, pec, synth, dev)
     if args.workload.startswith("decode"):
         return bench_decode(args, torch, np, pec, synth, dev)
+    if args.workload.startswith("ulysses"):
+        return bench_ulysses(args, torch, np, pec, synth, dev)
 
     w = synth.WORKLOADS[args.workload]
     S, C, Hq, Hkv = w.seq, w.chunk, w.n_q_heads, w.n_kv_heads
@@ -219,6 +221,45 @@ def bench_varlen(args, torch, np, pec, synth, dev):
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)]},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_ulysses(args, torch, np, pec, synth, dev):
+    """Head <-> sequence layout exchange (on-GPU half): segment of 16384 tokens, 64 heads, 8 GPUs."""
+    s_len, H, G = 16384, 64, 8
+    x = synth.randn_bf16((s_len, H, 128), 1006, dev)
+    y = torch.empty((G, s_len, H // G, 128), dtype=torch.bfloat16, device=dev)
+    z = torch.empty_like(x)
+    algo_bytes = 2.0 * x.numel() * 2            # read once, written once
+
+    def step():
+        pec.pec_ulysses_layout(x, G, True, out=y)
+        pec.pec_ulysses_layout(y, G, False, out=z)
+
+    for _ in range(max(args.warmup, 3)):
+        step()
+    torch.cuda.synchronize()
+    steps = max(args.steps, 20)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = ev0.elapsed_time(ev1) / steps / 2    # per kernel launch
+    gbs = algo_bytes / (ev_ms * 1e-3) / 1e9
+    assert torch.equal(z, x)
+    result = {
+        "metric": "Ulysses layout exchange, tokens/s through pack + unpack", "value": round(s_len / (ms_step * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 3), "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "ulysses_layout: [16384, 64, 128] bf16 <-> [8, 16384, 8, 128], both directions per step"},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+                     "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::ulysses_layout_kernel"},
     }
     print(json.dumps(result), flush=True)
     return 0

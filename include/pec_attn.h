@@ -163,6 +163,22 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
 int32_t pec_decode_default_splits(const pec_shape_t* shape, int64_t sk);
 size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits);
 
+/*
+ * On-GPU halves of the head <-> sequence exchange of Ulysses-style sequence parallelism (section
+ * "Sequence Parallelism of Megatron and Ulysses": an all-to-all turns "my sequence segment, all
+ * heads" into "the whole sequence, my heads" before attention, and back afterwards).  bf16,
+ * head_dim 128.
+ *   to_messages != 0: src [s, n_heads, 128] -> dst [n_gpus, s, n_heads/n_gpus, 128]; message g holds
+ *     the heads GPU g owns and is what the all-to-all sends to it.  (The messages a GPU receives,
+ *     ordered by source rank, already are its [n_gpus*s, n_heads/n_gpus, 128] input: no kernel.)
+ *   to_messages == 0: the inverse, src [n_gpus, s, n_heads/n_gpus, 128] (messages received after
+ *     attention, ordered by source rank) -> dst [s, n_heads, 128].
+ * src and dst must not overlap.  HBM-bound copy: every byte is read once and written once.
+ * The all-to-all itself is not part of this library.
+ */
+int pec_ulysses_layout(const void* src, void* dst, int64_t s, int32_t n_heads, int32_t head_dim, int32_t n_gpus,
+                       int to_messages, void* stream);
+
 /* Tuning knobs; process-wide, not thread-safe against concurrent calls. */
 enum {
     PEC_OPT_KERNEL_VARIANT = 0, /* see PEC_VARIANT_* */

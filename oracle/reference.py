@@ -199,6 +199,21 @@ def sp_prefill_states(q, k, v, *, q_off: int, chunk: int, causal: bool = True, s
     return states
 
 
+def ulysses_to_messages(x, n_gpus: int):
+    """Segment of all heads x [s, H, d] -> the G all-to-all messages [G, s, H/G, d]: message g holds
+    the heads GPU g owns (section "Sequence Parallelism of Megatron and Ulysses")."""
+    x = np.asarray(x)
+    s, h, d = x.shape
+    return np.ascontiguousarray(x.reshape(s, n_gpus, h // n_gpus, d).transpose(1, 0, 2, 3))
+
+
+def ulysses_from_messages(y):
+    """Inverse: received messages [G, s, H/G, d] (ordered by source rank) -> [s, H, d]."""
+    y = np.asarray(y)
+    g, s, hg, d = y.shape
+    return np.ascontiguousarray(y.transpose(1, 0, 2, 3).reshape(s, g * hg, d))
+
+
 def varlen(q, k, v, cu_seqlens, *, causal: bool = True, scale: float | None = None):
     """Packed batch: sequence b owns rows cu[b]..cu[b+1]-1 and attends only to itself."""
     qa, _ = _as_input(q)

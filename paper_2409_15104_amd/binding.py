@@ -28,8 +28,8 @@ PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
 
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
+    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_decode_default_splits",
+    "pec_decode_workspace_bytes", "pec_ulysses_layout", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
     "pec_get_option", "pec_status_string",
 )
 
@@ -73,6 +73,7 @@ def lib() -> ctypes.CDLL:
         L.pec_decode_default_splits.restype = i32
         L.pec_decode_workspace_bytes.argtypes = [sp, i32]
         L.pec_decode_workspace_bytes.restype = sz
+        L.pec_ulysses_layout.argtypes = [vp, vp, i64, i32, i32, i32, ci, vp]
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
@@ -81,7 +82,7 @@ def lib() -> ctypes.CDLL:
         L.pec_status_string.argtypes = [ci]
         L.pec_status_string.restype = ctypes.c_char_p
         for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-                     "pec_sp_prefill_step", "pec_decode_splitkv",
+                     "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout",
                      "pec_attn_varlen", "pec_set_option", "pec_get_option"):
             getattr(L, name).restype = ci
         _lib = L
@@ -260,6 +261,23 @@ def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scal
            lib().pec_decode_splitkv(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), sk, int(n_splits), _ptr(out),
                                     _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream)))
     return out, lse
+
+
+def pec_ulysses_layout(x, n_gpus: int, to_messages: bool, out=None, stream=None):
+    """to_messages: x [s,H,128] -> [G,s,H/G,128]; otherwise x [G,s,H/G,128] -> [s,H,128] (bf16)."""
+    _require(x, torch.bfloat16, "x")
+    if to_messages:
+        s, h, d = x.shape
+        shape = (n_gpus, s, h // n_gpus, d)
+    else:
+        g, s, hg, d = x.shape
+        h = g * hg
+        shape = (s, h, d)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.bfloat16, device=x.device)
+    _check("pec_ulysses_layout", lib().pec_ulysses_layout(_ptr(x), _ptr(out), s, h, d, int(n_gpus),
+                                                          int(bool(to_messages)), _stream(stream)))
+    return out
 
 
 def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:

@@ -87,6 +87,30 @@ __global__ __launch_bounds__(128) void combine_splits_kernel(const float* __rest
     if (d == 0) lse[h] = mx != -INFINITY ? mx + logf(den) : -INFINITY;
 }
 
+// Ulysses-style layout exchange, the on-GPU halves.  A GPU holding a sequence segment of all heads,
+// x [s, H, 128], packs it into G messages of s x H/G heads, y [G, s, H/G, 128] (message g = the heads
+// GPU g will own); the inverse turns G received messages back into [s, H, 128].  16 bytes per thread,
+// both sides contiguous in runs of H/G * 256 bytes.  TO_MESSAGES selects the direction.
+template <bool TO_MESSAGES>
+__global__ __launch_bounds__(256) void ulysses_layout_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                             int64_t s, int n_heads, int n_gpus) {
+    const int hg = n_heads / n_gpus;                 // heads per message
+    const int64_t chunks_per_tok = (int64_t)n_heads * 16;   // 16-byte chunks per token (all heads)
+    const int64_t total = s * chunks_per_tok;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        // i indexes the [s, H, 16] side
+        const int64_t t = i / chunks_per_tok;
+        const int r = (int)(i % chunks_per_tok);
+        const int h = r >> 4, c = r & 15;
+        const int g = h / hg, hh = h % hg;
+        const int64_t j = (((int64_t)g * s + t) * hg + hh) * 16 + c;   // index on the [G, s, H/G, 16] side
+        if constexpr (TO_MESSAGES)
+            dst[j] = src[i];
+        else
+            dst[i] = src[j];
+    }
+}
+
 // Work list for a packed batch: one item per (sequence, query tile), ordered by
 // descending query-tile index so the longest causal rows start first.  Single
 // workgroup; `bucket` and `cursor` are int32[max_qtiles] scratch.

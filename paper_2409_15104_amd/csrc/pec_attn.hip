@@ -397,6 +397,25 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
     return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
 }
 
+int pec_ulysses_layout(const void* src, void* dst, int64_t s, int32_t n_heads, int32_t head_dim, int32_t n_gpus,
+                       int to_messages, void* stream) {
+    if (s < 0 || n_heads <= 0 || n_gpus <= 0 || n_heads % n_gpus != 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (head_dim != kHeadDim) return PEC_ERR_UNSUPPORTED;
+    if (s > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (s == 0) return PEC_OK;
+    if (!src || !dst || src == dst) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(src) || misaligned(dst)) return PEC_ERR_MISALIGNED;
+    const int64_t total = s * n_heads * 16;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (to_messages)
+        hipLaunchKernelGGL((ulysses_layout_kernel<true>), dim3(grid_for(total)), dim3(256), 0, st,
+                           static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), s, (int)n_heads, (int)n_gpus);
+    else
+        hipLaunchKernelGGL((ulysses_layout_kernel<false>), dim3(grid_for(total)), dim3(256), 0, st,
+                           static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), s, (int)n_heads, (int)n_gpus);
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens) {
     if (batch < 0 || total_tokens < 0) return 0;
     const size_t cap = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;

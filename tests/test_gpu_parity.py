@@ -393,3 +393,16 @@ def test_decode_over_two_shards_merges_like_the_two_gpu_example():
     # all keys identical, Q = 0: every key weighs 1/sk, LSE = ln sk exactly
     _, l0 = pec.pec_decode_splitkv(torch.zeros_like(qd), kd, vd)
     assert np.all(np.rint(np.exp(l0.cpu().numpy().astype(np.float64))) == sk)
+
+
+@pytest.mark.parametrize("s,h,g", [(1, 8, 8), (333, 32, 4), (1000, 40, 8), (77, 64, 1), (0, 8, 2)])
+def test_ulysses_layout_is_bit_exact(s, h, g):
+    x = synth.randn_bf16((s, h, 128), 41 + s)
+    bits = x.view(torch.int16).numpy()
+    want = oracle.ulysses_to_messages(bits, g)
+    y = pec.pec_ulysses_layout(x.to(DEV), g, True)
+    assert y.shape == (g, s, h // g, 128)
+    assert np.array_equal(y.cpu().view(torch.int16).numpy(), want)
+    back = pec.pec_ulysses_layout(y, g, False)
+    assert np.array_equal(back.cpu().view(torch.int16).numpy(), oracle.ulysses_from_messages(want))
+    assert torch.equal(back.cpu(), x)

@@ -299,3 +299,23 @@ def test_input_recipe_statistics():
     assert synth.visible_pairs(3, 5, 0, 10, True) == 0
     assert synth.visible_pairs(4, 4, 2, 3, True) == sum(
         1 for i, j in itertools.product(range(4), range(4)) if 3 + j <= 2 + i)
+
+
+def test_ulysses_layout_is_the_all_to_all_of_a_head_sharded_view():
+    """Simulate the exchange on the CPU: G ranks each hold a sequence segment of all heads; after
+    packing, swapping message (r -> g) and concatenating by source rank, rank g must hold the whole
+    sequence of exactly its heads -- and the way back restores every segment."""
+    G, s, H, d = 4, 5, 8, 3
+    full = _rand((G * s, H, d), 70)                              # the whole sequence, all heads
+    segs = [full[r * s:(r + 1) * s] for r in range(G)]
+    msgs = [oracle.ulysses_to_messages(x, G) for x in segs]      # msgs[r][g]: from rank r to rank g
+    for g in range(G):
+        recv = np.stack([msgs[r][g] for r in range(G)])          # [G, s, H/G, d] ordered by source rank
+        want = full[:, g * (H // G):(g + 1) * (H // G)]          # whole sequence, rank g's heads
+        assert np.array_equal(recv.reshape(G * s, H // G, d), want)
+    # the way back: rank g sends rows r*s..(r+1)*s of its head shard to rank r
+    for r in range(G):
+        recv = np.stack([full[r * s:(r + 1) * s, g * (H // G):(g + 1) * (H // G)] for g in range(G)])
+        assert np.array_equal(oracle.ulysses_from_messages(recv), segs[r])
+    x = _rand((7, 6, 2), 71)
+    assert np.array_equal(oracle.ulysses_from_messages(oracle.ulysses_to_messages(x, 3)), x)
