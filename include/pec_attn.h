@@ -179,6 +179,38 @@ size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits);
 int pec_ulysses_layout(const void* src, void* dst, int64_t s, int32_t n_heads, int32_t head_dim, int32_t n_gpus,
                        int to_messages, void* stream);
 
+/*
+ * Intra-node strategy selection of fast Sequence Parallelism (section "Fast Sequence Parallelism for
+ * Long-Request Prefill"): for the attention stage and for the MLP stage either Megatron SP or Ulysses
+ * SP; the paper gives the communication volume per node and the computation volume per GPU of each
+ * choice in closed form, estimates the time of the four combinations and takes the smallest.  Host
+ * arithmetic only; no GPU work.  Volumes are in elements / flop exactly as the paper's formulas give
+ * them; the time estimate of a combination is, for both stages,
+ *     comm_elements * bytes_per_element / node_bandwidth + compute_flop / gpu_flops
+ * (the paper does not say how the two are combined; they are added).  Index 0 = Megatron, 1 = Ulysses.
+ */
+typedef struct {
+    int64_t d_model;          /* d */
+    int32_t n_heads;          /* N_h */
+    int32_t n_kv_heads;       /* N_h^KV */
+    int32_t head_dim;         /* d_h */
+    int64_t seg_len;          /* s: sequence segment length per GPU */
+    int32_t tp;               /* T: tensor-parallel size */
+    int32_t gpus_per_node;    /* G */
+    double bytes_per_element; /* 2 for bf16 */
+    double node_bandwidth;    /* bytes/s available to the node's collectives */
+    double gpu_flops;         /* flop/s one GPU sustains on these GEMMs / attention */
+} pec_sp_model_t;
+
+typedef struct {
+    double attn_comm[2], attn_compute[2]; /* attention stage: [Megatron, Ulysses] */
+    double mlp_comm[2], mlp_compute[2];   /* MLP stage */
+    double seconds[2][2];                 /* [attention choice][MLP choice] */
+    int32_t best_attn, best_mlp;          /* argmin of seconds (ties: Megatron first) */
+} pec_sp_choice_t;
+
+int pec_sp_select_strategy(const pec_sp_model_t* model, pec_sp_choice_t* choice);
+
 /* Tuning knobs; process-wide, not thread-safe against concurrent calls. */
 enum {
     PEC_OPT_KERNEL_VARIANT = 0, /* see PEC_VARIANT_* */

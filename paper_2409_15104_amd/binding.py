@@ -28,8 +28,8 @@ PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
 
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_ulysses_layout", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
+    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
+    "pec_decode_workspace_bytes", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
     "pec_get_option", "pec_status_string",
 )
 
@@ -37,6 +37,19 @@ EXPORTS = (
 class PecShape(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class PecSpModel(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int64), ("n_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("seg_len", ctypes.c_int64), ("tp", ctypes.c_int32),
+                ("gpus_per_node", ctypes.c_int32), ("bytes_per_element", ctypes.c_double),
+                ("node_bandwidth", ctypes.c_double), ("gpu_flops", ctypes.c_double)]
+
+
+class PecSpChoice(ctypes.Structure):
+    _fields_ = [("attn_comm", ctypes.c_double * 2), ("attn_compute", ctypes.c_double * 2),
+                ("mlp_comm", ctypes.c_double * 2), ("mlp_compute", ctypes.c_double * 2),
+                ("seconds", (ctypes.c_double * 2) * 2), ("best_attn", ctypes.c_int32), ("best_mlp", ctypes.c_int32)]
 
 
 class PecError(RuntimeError):
@@ -74,6 +87,7 @@ def lib() -> ctypes.CDLL:
         L.pec_decode_workspace_bytes.argtypes = [sp, i32]
         L.pec_decode_workspace_bytes.restype = sz
         L.pec_ulysses_layout.argtypes = [vp, vp, i64, i32, i32, i32, ci, vp]
+        L.pec_sp_select_strategy.argtypes = [ctypes.POINTER(PecSpModel), ctypes.POINTER(PecSpChoice)]
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
@@ -82,7 +96,7 @@ def lib() -> ctypes.CDLL:
         L.pec_status_string.argtypes = [ci]
         L.pec_status_string.restype = ctypes.c_char_p
         for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-                     "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout",
+                     "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy",
                      "pec_attn_varlen", "pec_set_option", "pec_get_option"):
             getattr(L, name).restype = ci
         _lib = L
@@ -278,6 +292,18 @@ def pec_ulysses_layout(x, n_gpus: int, to_messages: bool, out=None, stream=None)
     _check("pec_ulysses_layout", lib().pec_ulysses_layout(_ptr(x), _ptr(out), s, h, d, int(n_gpus),
                                                           int(bool(to_messages)), _stream(stream)))
     return out
+
+
+def pec_sp_select_strategy(d_model, n_heads, n_kv_heads, head_dim, seg_len, tp, gpus_per_node, bytes_per_element,
+                           node_bandwidth, gpu_flops) -> dict:
+    """Host-only: volumes and time estimates of the four Megatron/Ulysses combinations and the best one."""
+    m = PecSpModel(int(d_model), int(n_heads), int(n_kv_heads), int(head_dim), int(seg_len), int(tp),
+                   int(gpus_per_node), float(bytes_per_element), float(node_bandwidth), float(gpu_flops))
+    c = PecSpChoice()
+    _check("pec_sp_select_strategy", lib().pec_sp_select_strategy(ctypes.byref(m), ctypes.byref(c)))
+    return {"attn_comm": list(c.attn_comm), "attn_compute": list(c.attn_compute), "mlp_comm": list(c.mlp_comm),
+            "mlp_compute": list(c.mlp_compute), "seconds": [list(c.seconds[0]), list(c.seconds[1])],
+            "best": (int(c.best_attn), int(c.best_mlp))}
 
 
 def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:

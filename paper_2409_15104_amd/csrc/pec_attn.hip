@@ -416,6 +416,40 @@ int pec_ulysses_layout(const void* src, void* dst, int64_t s, int32_t n_heads, i
     return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
 }
 
+int pec_sp_select_strategy(const pec_sp_model_t* m, pec_sp_choice_t* c) {
+    if (!m || !c) return PEC_ERR_INVALID_ARGUMENT;
+    if (m->d_model <= 0 || m->n_heads <= 0 || m->n_kv_heads <= 0 || m->head_dim <= 0 || m->seg_len <= 0 ||
+        m->tp <= 0 || m->gpus_per_node <= 0 || !(m->bytes_per_element > 0) || !(m->node_bandwidth > 0) ||
+        !(m->gpu_flops > 0))
+        return PEC_ERR_INVALID_ARGUMENT;
+    const double d = (double)m->d_model, s = (double)m->seg_len, T = m->tp, G = m->gpus_per_node;
+    const double qkv = ((double)m->n_heads + m->n_kv_heads) * m->head_dim;   // (N_h + N_h^KV) d_h
+    // attention stage
+    c->attn_comm[0] = 2 * s * d * (T - 1) * G;                                           // all-gather + reduce-scatter
+    c->attn_compute[0] = 2 * s * d * qkv / T + 4 * (s * T) * (s * T) * d / T + 2 * s * d * d;
+    c->attn_comm[1] = 2 * s * qkv * (G - 1) + (d * qkv + d * d) * G * (T - 1) / T;       // two all-to-alls + parameters
+    c->attn_compute[1] = 2 * s * d * qkv + 4 * (s * G) * (s * G) * d / G + 2 * s * d * d;
+    // MLP stage
+    c->mlp_comm[0] = 2 * s * d * (T - 1) * G;
+    c->mlp_compute[0] = 16 * s * d * d;
+    c->mlp_comm[1] = 8 * d * d * (T - 1) * G / T;
+    c->mlp_compute[1] = 16 * s * d * d;
+    double best = 0;
+    c->best_attn = c->best_mlp = 0;
+    for (int a = 0; a < 2; ++a)
+        for (int l = 0; l < 2; ++l) {
+            const double t = (c->attn_comm[a] + c->mlp_comm[l]) * m->bytes_per_element / m->node_bandwidth +
+                             (c->attn_compute[a] + c->mlp_compute[l]) / m->gpu_flops;
+            c->seconds[a][l] = t;
+            if ((a == 0 && l == 0) || t < best) {
+                best = t;
+                c->best_attn = a;
+                c->best_mlp = l;
+            }
+        }
+    return PEC_OK;
+}
+
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens) {
     if (batch < 0 || total_tokens < 0) return 0;
     const size_t cap = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;
