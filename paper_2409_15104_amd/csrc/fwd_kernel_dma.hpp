@@ -270,7 +270,9 @@ __global__ __launch_bounds__(NWAVES * 64) void fwd_dma_kernel(const FwdParams p)
             l_run[nt] = l_run[nt] * alpha + rs;
             m_run[nt] = m_new;
             if (__any(alpha != 1.f)) {
-                // in-place multiply (tied operand) so the rarely taken branch costs no register copies
+                // in-place multiply (tied operand) so the rarely taken branch costs no register copies;
+                // the wait states cover an MFMA still writing O (inline asm gets no hazard handling)
+                asm volatile("s_nop 15\n\ts_nop 15");
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
 #pragma unroll

@@ -31,6 +31,10 @@ namespace pec {
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
+// The compiler's hazard recogniser does not look inside inline asm, and the hardware does not
+// interlock a VALU read of a register an MFMA is still writing: callers put mfma_settle() between
+// the last MFMA and the first scale_acc_in_place().
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15"); }
 __device__ __forceinline__ void scale_acc_in_place(f32x16& x, float a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x[r]) : "v"(a));
@@ -261,9 +265,10 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     // Softmax, split in two so that every iteration has VALU work that is ready from its first
     // cycle.  row_max(): mask / row maximum of a fresh score tile -> new running maximum and the
     // factor alpha by which everything accumulated so far shrinks.  weights(): exp2 of a score
-    // tile against the maximum fixed one iteration earlier -> P operands and the denominator.
-    float m_use = 0.f;    // maximum the pending tile's weights are taken against (0 for a row without keys)
-    float alpha = 1.f;    // exp2(previous maximum - m_use)
+    // tile against the reference fixed one iteration earlier -> P operands and the denominator.
+    constexpr float kRefSlack = 8.f;   // log2 units
+    float m_use = 0.f;    // reference the pending tile's weights are taken against (0 for a row without keys)
+    float alpha = 1.f;    // exp2(previous reference - m_use)
     auto row_max = [&](auto mask_tag, f32x16 (&s)[2], int key0) {
         constexpr bool MASK = decltype(mask_tag)::value;
         if constexpr (MASK) {
@@ -287,7 +292,12 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
             const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
             mx = fmaxf(__builtin_bit_cast(float, (uint32_t)sw[0]), __builtin_bit_cast(float, (uint32_t)sw[1]));
         }
-        const float m_new = fmaxf(m_run, mx * sl2);
+        // Lazy reference: any reference value gives the same softmax as long as numerator and
+        // denominator share it, so m_run only moves when the tile maximum exceeds it by more than
+        // kRefSlack (weights stay below 2^kRefSlack).  With the exact running maximum some row of a
+        // wavefront sets a new record in most tiles and O would be rescaled nearly every iteration.
+        const float mx2 = mx * sl2;
+        const float m_new = (mx2 > m_run + kRefSlack) ? mx2 : m_run;
         m_use = m_new;
         if constexpr (MASK) m_use = (m_new == -INFINITY) ? 0.f : m_new;   // only masked tiles can leave a row empty
         alpha = __builtin_amdgcn_exp2f(m_run - m_use);
@@ -386,6 +396,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
             }
         }
         if (__any(alpha_j != 1.f)) {
+            mfma_settle();
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha_j);
         }

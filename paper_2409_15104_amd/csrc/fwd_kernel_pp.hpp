@@ -290,7 +290,9 @@ __global__ __launch_bounds__(512) void fwd_pp_kernel(const FwdParams p) {
         // the weights must exist before the barrier that ends this block (keeps the exp work out of the MFMA block)
         asm volatile("" : "+v"(l_run), "+v"(m_run) : "v"(pf[0][0]), "v"(pf[0][1]), "v"(pf[1][0]), "v"(pf[1][1]));
         if (__any(alpha != 1.f)) {
-            // in-place multiply (tied operand): the rarely taken branch costs no register copies
+            // in-place multiply (tied operand): the rarely taken branch costs no register copies;
+            // wait states in case an MFMA is still writing O (inline asm gets no hazard handling)
+            asm volatile("s_nop 15\n\ts_nop 15");
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) scale_in_place(o[dt], alpha);
         }
