@@ -8,9 +8,13 @@
 // tile loop is software-pipelined in each wavefront: iteration j carries
 //     S(j+1) = K(j+1) Q^T               16 MFMAs
 //     O     += P(j-1) V(j-1)            16 MFMAs   (P(j-1) from the previous iteration)
-//     P(j)   = exp2(S(j) - m(j)) etc.   ~115 VALU  (S(j), m(j) from the previous iteration)
-//     m(j+1), alpha(j+1) from S(j+1)    ~25 VALU   (after the first 16 MFMAs)
-// which are independent of each other and get issued round-robin (about 4 VALU per MFMA).
+//     P(j)   = exp2(S(j) - m(j)) etc.   ~112 VALU  (S(j), m(j) from the previous iteration)
+//     m(j+1), alpha(j+1) from S(j+1)    ~30 VALU   (masked tiles only, after the first 16 MFMAs)
+// which are independent of each other and get issued round-robin (3 to 4 VALU per MFMA).
+// Measured: an MFMA of this shape keeps the SIMD's vector issue port for about 23 of its 32
+// cycles, so only 4 to 5 plain VALU instructions per MFMA are free; every one beyond that costs
+// about 2 cycles, a transcendental about 5.  Hence the softmax reference m is kept lazily
+// (see row_max) and unmasked tiles do without a row maximum (see body).
 // Same MFMA operand layouts, LDS swizzles and direct global->LDS tile loads as
 // fwd_kernel_dma.hpp; 8 wavefronts x 32 query rows; one workgroup barrier per tile.
 //
@@ -267,6 +271,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     // factor alpha by which everything accumulated so far shrinks.  weights(): exp2 of a score
     // tile against the reference fixed one iteration earlier -> P operands and the denominator.
     constexpr float kRefSlack = 8.f;   // log2 units
+    constexpr float kSumLimit = 65536.f;   // per-lane sum of 32 weights that triggers a reference update
     float m_use = 0.f;    // reference the pending tile's weights are taken against (0 for a row without keys)
     float alpha = 1.f;    // exp2(previous reference - m_use)
     auto row_max = [&](auto mask_tag, f32x16 (&s)[2], int key0) {
@@ -303,7 +308,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         alpha = __builtin_amdgcn_exp2f(m_run - m_use);
         m_run = m_new;
     };
-    auto weights = [&](const f32x16 (&s)[2], bf16x8 (&pp)[2][2]) {
+    auto weights_rs = [&](const f32x16 (&s)[2], bf16x8 (&pp)[2][2]) -> float {
         float rs = 0.f;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -319,6 +324,10 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                 }
                 pp[mt][t2] = __builtin_bit_cast(bf16x8, packed);
             }
+        return rs;
+    };
+    auto weights = [&](const f32x16 (&s)[2], bf16x8 (&pp)[2][2]) {
+        const float rs = weights_rs(s, pp);
         l_run = l_run * alpha + rs;
     };
 
@@ -340,8 +349,29 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         const unsigned char* v_rd = PAR ? lds_v0 : lds_v1;
         issue_k(j + 2, k_wr);
         issue_v(j, v_wr);
-        const float alpha_j = alpha;
-        if constexpr (PAR == 0) {
+        // An iteration whose next tile needs no mask skips the row maximum altogether: the weights of
+        // tile j are taken against the reference as it stands, and only a row sum above kSumLimit
+        // (some score far ahead of the reference) sends the wavefront through row_max() and a second
+        // pass over the tile, after the MFMAs.  Every row in such an iteration has a finite reference:
+        // tile 0 is fully visible to it and went through row_max() in the prologue.
+        constexpr bool FAST = DO_QK && !decltype(mask_next_tag)::value;
+        float alpha_j = alpha;
+        float rs_fast = 0.f;
+        if constexpr (FAST) {
+            if constexpr (PAR == 0) {
+                qk_mfma(s_b, k_rd);
+                pv_mfma(p_b, v_rd);
+                rs_fast = weights_rs(s_a, p_a);
+                asm volatile("" : "+v"(rs_fast), "+v"(m_run), "+v"(m_use), "+v"(alpha)
+                             : "v"(p_a[0][0]), "v"(p_a[0][1]), "v"(p_a[1][0]), "v"(p_a[1][1]));
+            } else {
+                qk_mfma(s_a, k_rd);
+                pv_mfma(p_a, v_rd);
+                rs_fast = weights_rs(s_b, p_b);
+                asm volatile("" : "+v"(rs_fast), "+v"(m_run), "+v"(m_use), "+v"(alpha)
+                             : "v"(p_b[0][0]), "v"(p_b[0][1]), "v"(p_b[1][0]), "v"(p_b[1][1]));
+            }
+        } else if constexpr (PAR == 0) {
             if constexpr (DO_QK) qk_mfma(s_b, k_rd);
             pv_mfma(p_b, v_rd);
             weights(s_a, p_a);
@@ -395,6 +425,23 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                 __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
             }
         }
+        if constexpr (FAST) {
+            if (__any(!(rs_fast <= kSumLimit))) {   // also catches an overflowed (infinite) sum
+                const float a_pending = alpha;
+                if constexpr (PAR == 0) {
+                    row_max(std::false_type{}, s_a, j * kBN);
+                    rs_fast = weights_rs(s_a, p_a);
+                } else {
+                    row_max(std::false_type{}, s_b, j * kBN);
+                    rs_fast = weights_rs(s_b, p_b);
+                }
+                alpha *= a_pending;
+            }
+            l_run = l_run * alpha + rs_fast;
+            alpha_j = alpha;
+            alpha = 1.f;        // nothing pending for tile j + 1: its reference is the current one
+            m_use = m_run;
+        }
         if (__any(alpha_j != 1.f)) {
             mfma_settle();
 #pragma unroll
@@ -426,6 +473,12 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     for (; j < e1; j += 2) {
         body(P0{}, F{}, T{}, j);
         body(P1{}, F{}, T{}, j + 1);
+    }
+    if (e1 > 0) {
+        // S(e1) left the unmasked run without a row maximum, and the iterations below take their
+        // tile's weights without the overflow check: settle its reference here, once
+        row_max(F{}, s_a, e1 * kBN);
+        asm volatile("" : "+v"(m_run), "+v"(m_use), "+v"(alpha));
     }
     for (; j + 1 < n_act - 1; j += 2) {
         body(P0{}, T{}, T{}, j);

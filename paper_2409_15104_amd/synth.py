@@ -59,6 +59,23 @@ def qkv(seed: int, s_q: int, s_kv: int, n_q_heads: int, n_kv_heads: int, d: int 
     return q, k, v
 
 
+def qkv_with_outlier_keys(seed: int, s_q: int, s_kv: int, n_q_heads: int, n_kv_heads: int, outliers, d: int = HEAD_DIM,
+                          device="cpu"):
+    """``qkv`` with some key rows replaced by multiples of query rows.
+
+    ``outliers`` is a list of (key_pos, query_row, gain): key ``key_pos`` of every KV head becomes
+    ``gain`` times query row ``query_row`` of the first query head of that group, so that row's score
+    against the key lies about ``gain * sqrt(d)`` above the N(0,1) bulk -- a jump of the running softmax
+    maximum late in the key stream.
+    """
+    q, k, v = qkv(seed, s_q, s_kv, n_q_heads, n_kv_heads, d, device)
+    group = n_q_heads // n_kv_heads
+    k = k.clone()
+    for key_pos, row, gain in outliers:
+        k[key_pos] = (q[row, ::group].float() * float(gain)).to(k.dtype)
+    return q, k, v
+
+
 def lognormal_lengths(seed: int, n: int = VARLEN_N_SHORT, median: float = 700.0, p80: float = 2048.0,
                       max_len: int = 8192) -> np.ndarray:
     """Prompt lengths L = clip(round(exp(mu + sigma z)), 1, max_len), z ~ N(0,1).

@@ -79,6 +79,26 @@ def test_chunk_matches_oracle(case, variant):
         assert_close(out, lse, o_ref, l_ref, "chunk %s v%d %s" % (case, variant, out_dtype))
 
 
+@pytest.mark.parametrize("variant", VARIANTS[:4])
+@pytest.mark.parametrize("q_off", [0, 4096])
+def test_late_jumps_of_the_row_maximum(q_off, variant):
+    # keys that lift single rows' scores 16 ... 130 log2 units above the bulk, placed in tiles after the
+    # first one, in masked (diagonal) and unmasked tiles: the kernels' softmax reference has to follow
+    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
+    s = 1024
+    outliers = [(70, 950, 1), (300, 400, 2), (301, 1000, 4), (640, 700, 8), (900, 901, 8), (999, 1023, 2),
+                (130, 5, 4), (515, 33, 1)]   # the last two are invisible under the causal mask when q_off = 0
+    q, k, v = synth.qkv_with_outlier_keys(4242, s, s, 8, 2, outliers)
+    o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, 0, True, out_dtype=torch.float32)
+    assert_close(out, lse, o_ref, l_ref, "outlier keys q_off %d v%d" % (q_off, variant))
+    # and continued from a first half computed separately (fused merge across the jump)
+    h = s // 2
+    o1, l1 = pec.pec_attn_chunk(*gpu(q, k[:h].contiguous(), v[:h].contiguous()), q_off, 0, True, out_dtype=torch.float32)
+    o2, l2 = pec.pec_attn_chunk_merge(*gpu(q, k[h:].contiguous(), v[h:].contiguous()), q_off, h, o1, l1, True)
+    assert_close(o2, l2, o_ref, l_ref, "outlier keys, two segments, q_off %d v%d" % (q_off, variant))
+
+
 def test_chunk_empty_query_is_a_noop():
     q, k, v = synth.qkv(3, 0, 16, 2, 2)
     out, lse = pec.pec_attn_chunk(*gpu(q, k, v), 0, 0)
