@@ -53,17 +53,27 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds_v0[kTileBytes];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_v1[kTileBytes];
 
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63;
-    const int l32 = lane & 31;
-    const int hl = lane >> 5;
-
-    // ---- block -> (kv head, work item, head in group), one contiguous logical range per XCD
+    // ---- persistent workgroups: the grid holds n_slots workgroups per XCD (hardware deals block
+    // ids round-robin over the 8 XCDs); each XCD owns one contiguous logical range of the
+    // (KV-head-major, longest-rows-first) work order and its workgroups walk it in snake order
+    // (slot, then reversed slot, ...), which evens out the causal length differences.
     const int64_t total = (int64_t)p.n_items * p.n_q_heads;
     const int64_t per_xcd = (total + 7) >> 3;
-    const int64_t logical = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= total) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_slots = (int)(gridDim.x >> 3);
+    const int slot = (int)(blockIdx.x >> 3);
+    for (int64_t round0 = 0; round0 < per_xcd; round0 += n_slots) {
+    // Lane-derived values are recomputed for every work item (the empty asm hides that they are
+    // loop invariant): hoisted out of this loop they would stay live through the tile loop, which
+    // has no register to spare -- a spill reload there waits on the tile loads just issued.
+    int lane;   // volatile asm: not hoisted, and no vector register carries it from item to item
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+    const int l32 = lane & 31;
+    const int hl = lane >> 5;
+    const int64_t idx_in_xcd = round0 + (((round0 / n_slots) & 1) ? (n_slots - 1 - slot) : slot);
+    if (idx_in_xcd >= per_xcd) continue;
+    const int64_t logical = (int64_t)(blockIdx.x & 7) * per_xcd + idx_in_xcd;
+    if (logical >= total) continue;
     const int per_kvh = p.n_items * p.group;
     const int kvh = (int)(logical / per_kvh);
     const int rem = (int)(logical % per_kvh);
@@ -73,7 +83,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     int sq, sk, delta, qt;
     int64_t q_tok0, kv_tok0;
     if (p.cu_seqlens) {
-        if (item >= *p.n_work) return;
+        if (item >= *p.n_work) continue;
         const WorkItem w = p.work[item];
         const int b0 = min(max(p.cu_seqlens[w.seq], 0), p.total_tokens);
         const int b1 = min(max(p.cu_seqlens[w.seq + 1], b0), p.total_tokens);
@@ -195,12 +205,17 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
 #pragma unroll
             for (int it = 0; it < 2; ++it) dma16(tb + it * block_stride_b, full_off0, lds0 + it * NWAVES * 1024);
         } else {   // rows past the end re-read the last valid row: finite data, weight zero
+            // (at most once per work item: everything is rebuilt from the lane id here, so that the
+            // tile loop carries no register for this path)
+            int ln;
+            asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln));
+            const int r_row = ln >> 4, r_pos = ln & 15;
             const int last = sk - 1 - key0;
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
-                const int key = 4 * (it * NWAVES + wave) + ld_row;
-                const uint32_t col = is_v ? (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u
-                                          : (uint32_t)(ld_pos ^ (key & 15)) * 16u;
+                const int key = 4 * (it * NWAVES + wave) + r_row;
+                const uint32_t col = is_v ? (uint32_t)((((r_pos >> 2) ^ (key & 3)) << 2) | (r_pos & 3)) * 16u
+                                          : (uint32_t)(r_pos ^ (key & 15)) * 16u;
                 dma16(tb, (uint32_t)min(key, last) * kv_stride_b + col, lds0 + it * NWAVES * 1024);
             }
         }
@@ -332,7 +347,11 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     };
 
     auto end_of_iteration = [&]() {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's tile loads have landed
+        // vmcnt(0): this wavefront's tile loads have landed.  Issued through the builtin so that the
+        // compiler's own counter bookkeeping knows nothing is outstanding here: it cannot see the
+        // asm tile loads, and a leftover wait of its own inside the loop would stall on them.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt 0, expcnt / lgkmcnt unconstrained
+        asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
     };
 
@@ -388,9 +407,9 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         }
         // issue order: operand fragments a few MFMAs ahead; after every MFMA a slice of the softmax
         if constexpr (DO_QK) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-            for (int i = 0; i < 10; ++i) {   // QK MFMAs, remaining K fragments
+            for (int i = 0; i < 12; ++i) {   // QK MFMAs, remaining K fragments
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
@@ -404,22 +423,22 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                 __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
             }
 #pragma unroll
-            for (int i = 0; i < 6; ++i) {
+            for (int i = 0; i < 4; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
             }
         } else {
-            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-            for (int i = 0; i < 12; ++i) {
+            for (int i = 0; i < 14; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
                 __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
                 __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
@@ -532,6 +551,8 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                 }
         }
     }
+    __builtin_amdgcn_s_barrier();   // every wavefront is done with the LDS stages before the next item's loads
+    }   // work items of this workgroup
 }
 
 }  // namespace pec

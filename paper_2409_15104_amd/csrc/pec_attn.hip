@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 
 #include "aux_kernels.hpp"
 #include "fwd_kernel.hpp"
@@ -36,8 +37,24 @@ void launch_pp(const FwdParams& p, unsigned grid, hipStream_t st) {
     (void)attr;
     hipLaunchKernelGGL((fwd_pp_kernel<PAIR_STRIDE4>), dim3(grid), dim3(512), kPpLdsBytes, st, p);
 }
+// Compute units of the current device (cached per device id).
+int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+// The interleaved kernel is persistent: one workgroup per compute unit (its registers allow no
+// second one), each walking its share of the `grid` logical work items.
 void launch_il(const FwdParams& p, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL(fwd_il_kernel, dim3(grid), dim3(512), 0, st, p);
+    const unsigned per_xcd = grid / 8;
+    const unsigned slots = std::max(1u, std::min(per_xcd, (unsigned)compute_units() / 8));
+    hipLaunchKernelGGL(fwd_il_kernel, dim3(8 * slots), dim3(512), 0, st, p);
 }
 struct Variant {
     int bm;
