@@ -26,7 +26,7 @@ FLOP_PER_PAIR = 512.0          # per (query, key, head): 2*128 for q.k plus 2*12
 # HBM bytes per launch of the dominant kernel (read + written), averaged over the launches of one sweep,
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a device copy of known size
 # (profiles/fwd_il_kernel_c3_gqa_128k_hbm_traffic.md).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"c3_gqa_128k": 4.726e8}
+MEASURED_TRAFFIC_BYTES = {"c3_gqa_128k": 4.849e8}
 
 
 def parse_args():
