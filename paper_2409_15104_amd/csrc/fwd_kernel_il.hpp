@@ -445,8 +445,9 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
             }
         }
         if constexpr (FAST) {
+            // no factor is pending on entry (the prologue applies its own), so the one test decides
+            // everything; alpha_j is only set on the rare path
             if (__any(!(rs_fast <= kSumLimit))) {   // also catches an overflowed (infinite) sum
-                const float a_pending = alpha;
                 if constexpr (PAR == 0) {
                     row_max(std::false_type{}, s_a, j * kBN);
                     rs_fast = weights_rs(s_a, p_a);
@@ -454,17 +455,20 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                     row_max(std::false_type{}, s_b, j * kBN);
                     rs_fast = weights_rs(s_b, p_b);
                 }
-                alpha *= a_pending;
-            }
-            l_run = l_run * alpha + rs_fast;
-            alpha_j = alpha;
-            alpha = 1.f;        // nothing pending for tile j + 1: its reference is the current one
-            m_use = m_run;
-        }
-        if (__any(alpha_j != 1.f)) {
-            mfma_settle();
+                l_run *= alpha;
+                mfma_settle();
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha_j);
+                for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha);
+                alpha = 1.f;        // nothing pending for tile j + 1: its reference is the current one
+                m_use = m_run;
+            }
+            l_run += rs_fast;
+        } else {
+            if (__any(alpha_j != 1.f)) {
+                mfma_settle();
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha_j);
+            }
         }
         end_of_iteration();
     };
@@ -481,6 +485,16 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     if (n_act > 0) {
         qk_mfma(s_a, lds_k0);
         row_max(T{}, s_a, 0);
+        // the factor tile 0 puts on what was carried in is applied here, so that the unmasked
+        // iterations start with nothing pending
+        l_run *= alpha;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        }
+        alpha = 1.f;
     }
     asm volatile("" : "+v"(s_a[0]), "+v"(s_a[1]), "+v"(m_run), "+v"(m_use), "+v"(alpha));
     __builtin_amdgcn_s_barrier();     // K stage 0 may be overwritten from here on
