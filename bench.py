@@ -12,6 +12,7 @@ in HBM before the timed region.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import math
 import os
@@ -39,6 +40,7 @@ def parse_args():
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--decode-splits", type=int, default=0, help="key ranges per KV head for --workload decode_512k (0: library default)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three 1 GiB device-to-device copies (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -270,10 +272,11 @@ def bench_decode(args, torch, np, pec, synth, dev):
     HBM-bound: K and V are read once."""
     Hq, Hkv, sk = 64, 8, 524288
     q, k, v = synth.qkv(1005, 1, sk, Hq, Hkv, device=dev)
-    n_splits = 256 // Hkv        # the library's default for this shape: one workgroup per compute unit
+    shp = pec.PecShape(Hq, Hkv, 128, 1, 0.0)
+    n_splits = args.decode_splits or int(pec.lib().pec_decode_default_splits(ctypes.byref(shp), sk))   # key ranges per KV head
     out = torch.empty((1, Hq, 128), dtype=torch.float32, device=dev)
     lse = torch.empty((Hq,), dtype=torch.float32, device=dev)
-    ws = torch.empty(1 << 22, dtype=torch.uint8, device=dev)
+    ws = torch.empty(n_splits * Hq * 129 * 4, dtype=torch.uint8, device=dev)
     algo_bytes = 2.0 * sk * Hkv * 128 * 2 + 2 * Hq * 128 * 2 + Hq * 4      # K + V once, q, out, lse
 
     def step():
@@ -300,7 +303,7 @@ def bench_decode(args, torch, np, pec, synth, dev):
         "config": {"workload": "decode_512k: 1 query token, 64 q / 8 kv heads, KV shard of 524288 tokens, %d key splits"
                                % n_splits},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
-                     "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::fwd_il_kernel (split-KV) + combine"},
+                     "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::decode_kernel + pec::combine_splits_kernel"},
     }
     print(json.dumps(result), flush=True)
     return 0

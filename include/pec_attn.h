@@ -150,8 +150,9 @@ size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens);
  * Decode attention of a long request kept on its prefill GPUs while short prefills share them
  * (section "Coordinated Prefill-Decode Colocation and Disaggregation"): ONE new token, q [1, Hq, 128],
  * against this GPU's shard of the KV cache, k/v [sk, Hkv, 128]; every key is visible.  The shard is
- * cut into n_splits key ranges processed by separate workgroups (0 = pick a default), the partial
- * (O, LSE) pairs are combined exactly by log-sum-exp.  out [1, Hq, 128] in shape->out_dtype and
+ * cut into n_splits key ranges (0 = pick a default: one workgroup per compute unit), each KV head of
+ * a range is streamed by one wavefront on its own, the partial (O, LSE) pairs are combined exactly
+ * by log-sum-exp.  out [1, Hq, 128] in shape->out_dtype and
  * lse [Hq] form a partial pair over this shard: results of several shards / GPUs (the paper's
  * example merges the outputs of two GPUs) combine with pec_attn_merge (use out_dtype PEC_F32).
  * sk == 0 gives out = 0, lse = -inf.  workspace: pec_decode_workspace_bytes() bytes.

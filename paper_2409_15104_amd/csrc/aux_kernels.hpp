@@ -61,30 +61,56 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
 
 // Combines the partial results of a split-KV decode: for every head, L = ln sum_s exp(lse_s) and
 // O = sum_s O_s exp(lse_s - L) over the n_splits disjoint key ranges (the two-set merge applied to
-// all ranges at once).  One workgroup of 128 threads per head; partials are fp32
-// [n_splits][n_heads][128] and [n_splits][n_heads].
+// all ranges at once).  One workgroup per head, kCombineGroups x 128 threads: thread (grp, d) sums
+// the ranges s = grp, grp + kCombineGroups, ... for dimension d, LDS adds the groups up.  Partials
+// are fp32 [n_splits][n_heads][128] and [n_splits][n_heads].
+constexpr int kCombineGroups = 8;
 template <bool OUT_F32>
-__global__ __launch_bounds__(128) void combine_splits_kernel(const float* __restrict__ o_part,
-                                                             const float* __restrict__ lse_part, int n_splits,
-                                                             int n_heads, void* __restrict__ out,
-                                                             float* __restrict__ lse) {
-    const int h = blockIdx.x, d = threadIdx.x;
+__global__ __launch_bounds__(kCombineGroups * 128) void combine_splits_kernel(const float* __restrict__ o_part,
+                                                                              const float* __restrict__ lse_part,
+                                                                              int n_splits, int n_heads,
+                                                                              void* __restrict__ out,
+                                                                              float* __restrict__ lse) {
+    __shared__ float red[kCombineGroups][kHeadDim];
+    __shared__ float red_s[kCombineGroups * 2];
+    const int h = blockIdx.x, d = threadIdx.x & 127, grp = threadIdx.x >> 7;
+    const int tid = threadIdx.x, nthr = kCombineGroups * 128;
+    // maximum LSE of the head: every wavefront reduces its share, LDS the 16 wavefronts
     float mx = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, lse_part[(int64_t)s * n_heads + h]);
+    for (int s = tid; s < n_splits; s += nthr) mx = fmaxf(mx, lse_part[(int64_t)s * n_heads + h]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((tid & 63) == 0) red_s[tid >> 6] = mx;
+    __syncthreads();
+    mx = red_s[0];
+#pragma unroll
+    for (int w = 1; w < kCombineGroups * 2; ++w) mx = fmaxf(mx, red_s[w]);
     float den = 0.f, acc = 0.f;
     if (mx != -INFINITY) {
-        for (int s = 0; s < n_splits; ++s) {
+        for (int s = grp; s < n_splits; s += kCombineGroups) {
             const float w = expf(lse_part[(int64_t)s * n_heads + h] - mx);
-            den += w;
+            den += w;   // every thread of a group carries the group's share of the denominator
             acc += w * o_part[((int64_t)s * n_heads + h) * kHeadDim + d];
         }
-        acc /= den;
     }
-    if constexpr (OUT_F32)
-        reinterpret_cast<float*>(out)[(int64_t)h * kHeadDim + d] = acc;
-    else
-        reinterpret_cast<__bf16*>(out)[(int64_t)h * kHeadDim + d] = (__bf16)acc;
-    if (d == 0) lse[h] = mx != -INFINITY ? mx + logf(den) : -INFINITY;
+    red[grp][d] = acc;
+    __syncthreads();                 // also orders the reads of red_s above before its reuse below
+    if (d == 0) red_s[grp] = den;
+    __syncthreads();
+    if (grp == 0) {
+        float a = 0.f, dn = 0.f;
+#pragma unroll
+        for (int g2 = 0; g2 < kCombineGroups; ++g2) {
+            a += red[g2][d];
+            dn += red_s[g2];
+        }
+        if (mx != -INFINITY) a /= dn;
+        if constexpr (OUT_F32)
+            reinterpret_cast<float*>(out)[(int64_t)h * kHeadDim + d] = a;
+        else
+            reinterpret_cast<__bf16*>(out)[(int64_t)h * kHeadDim + d] = (__bf16)a;
+        if (d == 0) lse[h] = mx != -INFINITY ? mx + logf(dn) : -INFINITY;
+    }
 }
 
 // Ulysses-style layout exchange, the on-GPU halves.  A GPU holding a sequence segment of all heads,

@@ -10,6 +10,7 @@
 #include <cstdlib>
 
 #include "aux_kernels.hpp"
+#include "decode_kernel.hpp"
 #include "fwd_kernel.hpp"
 #include "fwd_kernel_dma.hpp"
 #include "fwd_kernel_il.hpp"
@@ -349,9 +350,13 @@ int pec_sp_prefill_step(const pec_shape_t* shape, const void* q, const void* k, 
 
 int32_t pec_decode_default_splits(const pec_shape_t* shape, int64_t sk) {
     if (!shape || shape->n_kv_heads <= 0 || sk <= 0) return 1;
-    // one workgroup per compute unit measured best (256 CUs / n_kv_heads key ranges), with at
-    // least 16 tiles of 64 keys per range
-    const int64_t per_cu = std::max<int64_t>(1, 256 / shape->n_kv_heads);
+    const int g = shape->n_q_heads / shape->n_kv_heads;
+    const int64_t per_cu = std::max<int64_t>(1, compute_units() / shape->n_kv_heads);
+    if (g <= 32) {   // one workgroup (four KV heads of one range) per compute unit, at least 8 tiles of 32 keys each
+        const int64_t head_groups = (shape->n_kv_heads + kDecWaves - 1) / kDecWaves;
+        return (int32_t)std::max<int64_t>(1, std::min<int64_t>(compute_units() / head_groups, sk / 256));
+    }
+    // wide groups run on the prefill kernel: one workgroup per compute unit, at least 16 tiles of 64 keys each
     return (int32_t)std::max<int64_t>(1, std::min<int64_t>(per_cu, sk / 1024));
 }
 
@@ -377,6 +382,27 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
     float* lse_part = o_part + (size_t)n_splits * shape->n_q_heads * kHeadDim;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
+    if (g <= 32) {   // one key range per wavefront (decode_kernel.hpp)
+        DecodeParams d{};
+        d.q = static_cast<const __bf16*>(q);
+        d.k = static_cast<const unsigned char*>(k);
+        d.v = static_cast<const unsigned char*>(v);
+        d.o_part = o_part;
+        d.lse_part = lse_part;
+        d.sk = (int32_t)sk;
+        d.n_q_heads = shape->n_q_heads;
+        d.n_kv_heads = shape->n_kv_heads;
+        d.group = g;
+        d.n_ranges = n_splits;
+        const int64_t per = ((sk + n_splits - 1) / n_splits + kDecTile - 1) / kDecTile * kDecTile;
+        d.range_len = (int32_t)std::max<int64_t>(per, kDecTile);
+        d.scale_log2 = scale * kLog2e;
+        const int64_t blocks = (int64_t)n_splits * ((shape->n_kv_heads + kDecWaves - 1) / kDecWaves);
+        const int64_t grid = ((blocks + 7) / 8) * 8;
+        if (grid > 0x7fffffffLL) return PEC_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(decode_kernel, dim3((unsigned)grid), dim3(kDecWaves * 64), 0, st, d);
+        if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+    } else {
     // The g query heads of one KV head become the g rows of one query tile: row stride 128, "head"
     // (= KV head) stride g*128; the work items are the key ranges.
     FwdParams p{};
@@ -405,11 +431,12 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
     const int64_t total = (int64_t)n_splits * shape->n_kv_heads;
     launch_il(p, (unsigned)(((total + 7) / 8) * 8), st);
     if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+    }
     if (shape->out_dtype == PEC_F32)
-        hipLaunchKernelGGL((combine_splits_kernel<true>), dim3(shape->n_q_heads), dim3(128), 0, st, o_part, lse_part,
+        hipLaunchKernelGGL((combine_splits_kernel<true>), dim3(shape->n_q_heads), dim3(kCombineGroups * 128), 0, st, o_part, lse_part,
                            (int)n_splits, (int)shape->n_q_heads, out, lse);
     else
-        hipLaunchKernelGGL((combine_splits_kernel<false>), dim3(shape->n_q_heads), dim3(128), 0, st, o_part, lse_part,
+        hipLaunchKernelGGL((combine_splits_kernel<false>), dim3(shape->n_q_heads), dim3(kCombineGroups * 128), 0, st, o_part, lse_part,
                            (int)n_splits, (int)shape->n_q_heads, out, lse);
     return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
 }

@@ -388,7 +388,11 @@ def test_resumable_prefill_states_match_oracle_and_survive_preemption():
 
 
 @pytest.mark.parametrize("sk,hq,hkv,n_splits", [(1, 8, 8, 0), (63, 8, 2, 1), (64, 4, 4, 3), (700, 32, 8, 0),
-                                                (5000, 64, 8, 7), (70000, 32, 8, 0), (0, 8, 2, 0)])
+                                                (5000, 64, 8, 7), (70000, 32, 8, 0), (0, 8, 2, 0),
+                                                (33, 12, 3, 0),        # three KV heads: a workgroup with an idle wavefront
+                                                (3000, 40, 5, 300),    # more ranges than tiles: most ranges are empty
+                                                (2100, 64, 1, 3),      # 64 heads on one KV head: the wide-group path
+                                                (4097, 32, 1, 0)])     # 32 heads on one KV head: every query column in use
 def test_decode_splitkv_matches_oracle(sk, hq, hkv, n_splits):
     """One new token against a KV-cache shard (long-request decode colocated with short prefills)."""
     q, k, v = synth.qkv(31 + sk, 1, sk, hq, hkv)
