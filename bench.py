@@ -7,7 +7,7 @@ order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen|decode_512k|ulysses_layout]
-                  [--sp-mode fused|separate|single] [--variant N] [--no-cpu-baseline]
+                  [--sp-mode fused|separate|single] [--variant N] [--share] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--workload", default="c3_gqa_128k")
     ap.add_argument("--sp-mode", default="fused", choices=["fused", "separate", "single"])
     ap.add_argument("--variant", type=int, default=None)
+    ap.add_argument("--share", action="store_true",
+                    help="time one GPU's share only: the last ring member's prefill (its query segment against all KV segments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--decode-splits", type=int, default=0, help="key ranges per KV head for --workload decode_512k (0: library default)")
@@ -88,6 +90,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     S, C, Hq, Hkv = w.seq, w.chunk, w.n_q_heads, w.n_kv_heads
     P = S // C
+    if args.share:
+        return bench_share(args, torch, pec, synth, dev, w, mode)
     q, k, v = synth.qkv(w.seed, S, S, Hq, Hkv, device=dev)
     out = torch.empty_like(q)
     lse = torch.empty((P, Hq, C), dtype=torch.float32, device=dev)   # one [Hq, C] block per ring member
@@ -145,6 +149,55 @@ def main():
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, np, torch, synth, q, k, v, w)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_share(args, torch, pec, synth, dev, w, mode):
+    """One GPU's share of the ring: the last member's query segment against every KV segment (what a GPU of
+    the sequence-parallel group computes; the other members' shares are smaller under the causal mask)."""
+    S, C, Hq, Hkv = w.seq, w.chunk, w.n_q_heads, w.n_kv_heads
+    P = S // C
+    q, k, v = synth.qkv(w.seed, C, S, Hq, Hkv, device=dev)      # Q of the one segment only
+    out = torch.empty_like(q)
+    lse = torch.empty((Hq, C), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C)), dtype=torch.uint8, device=dev)
+    lo = S - C
+    flops = FLOP_PER_PAIR * Hq * synth.visible_pairs(C, S, lo, 0, True)
+    launches = P if mode != pec.PEC_SP_SINGLE_LAUNCH else 1
+
+    def step():
+        pec.pec_sp_prefill(q, k, v, lo, C, True, out=out, lse=lse, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    avg_launch_ms = ev0.elapsed_time(ev1) / args.steps / launches
+    tflops = flops / (ms_step * 1e-3) / 1e12
+    achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
+    result = {
+        "metric": "prefill attention TFLOP/s of one ring member's share; % of bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s, last member's share: %d query rows at offset %d against %d keys in %d segments, "
+                               "%d q heads / %d kv heads, LSE merge (%s)" % (w.name, C, lo, S, P, Hq, Hkv, args.sp_mode)},
+        "tokens_per_s": round(C / (ms_step * 1e-3), 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "causal_useful_tflop_per_step": round(flops / 1e12, 3),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)],
+                     "launches_per_step": launches, "avg_launch_ms": round(avg_launch_ms, 4)},
+    }
     print(json.dumps(result), flush=True)
     return 0
 
