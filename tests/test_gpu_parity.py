@@ -99,6 +99,25 @@ def test_late_jumps_of_the_row_maximum(q_off, variant):
     assert_close(o2, l2, o_ref, l_ref, "outlier keys, two segments, q_off %d v%d" % (q_off, variant))
 
 
+def test_late_jumps_in_a_packed_batch_and_without_a_mask():
+    # the same outlier keys inside one sequence of a packed batch, and in a non-causal call whose last
+    # tile is ragged
+    lengths = [200, 1024, 77]
+    cu = synth.cu_seqlens_of(lengths)
+    t = int(cu[-1])
+    lo = int(cu[1])
+    outliers = [(lo + 70, lo + 950, 2), (lo + 640, lo + 700, 8), (lo + 900, lo + 901, 4), (10, 150, 8)]
+    q, k, v = synth.qkv_with_outlier_keys(4343, t, t, 8, 2, outliers)
+    o_ref, l_ref = oracle.varlen(q, k, v, cu)
+    out, lse = pec.pec_attn_varlen(*gpu(q, k, v), torch.from_numpy(cu).to(DEV), max(lengths), True,
+                                   out_dtype=torch.float32)
+    assert_close(out, lse, o_ref, l_ref, "outlier keys, packed batch")
+    q, k, v = synth.qkv_with_outlier_keys(4344, 300, 1000, 4, 4, [(500, 17, 8), (998, 250, 2), (999, 299, 8)])
+    o_ref, l_ref = oracle.attention(q, k, v, causal=False)
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), 0, 0, False, out_dtype=torch.float32)
+    assert_close(out, lse, o_ref, l_ref, "outlier keys, non-causal")
+
+
 def test_chunk_empty_query_is_a_noop():
     q, k, v = synth.qkv(3, 0, 16, 2, 2)
     out, lse = pec.pec_attn_chunk(*gpu(q, k, v), 0, 0)
