@@ -421,6 +421,16 @@ def test_decode_splitkv_matches_oracle(sk, hq, hkv, n_splits):
         assert_close(out, lse.reshape(hq, 1), o_ref, l_ref, "decode sk=%d %s" % (sk, out_dtype))
 
 
+def test_decode_with_late_jumps_of_the_maximum():
+    # keys far above the bulk late in the cache, in different key ranges
+    sk, hq, hkv = 6000, 16, 4
+    q, k, v = synth.qkv_with_outlier_keys(4545, 1, sk, hq, hkv, [(100, 0, 1), (2500, 0, 4), (5990, 0, 8)])
+    o_ref, l_ref = oracle.attention(q, k, v, causal=False)
+    for n_splits in (0, 1, 5):
+        out, lse = pec.pec_decode_splitkv(*gpu(q, k, v), n_splits=n_splits, out_dtype=torch.float32)
+        assert_close(out, lse.reshape(hq, 1), o_ref, l_ref, "decode with outlier keys, %d ranges" % n_splits)
+
+
 def test_decode_over_two_shards_merges_like_the_two_gpu_example():
     """The long request's KV cache lives on two GPUs; each computes its partial, the partials are
     merged (here: both shards on the one GPU, merged with pec_attn_merge)."""
