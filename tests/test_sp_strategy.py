@@ -12,12 +12,42 @@ from paper_2409_15104_amd import binding as pec
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "sp_cost_example.txt")
 
 
-def test_volumes_match_the_hand_evaluated_example():
-    rows = [ln.split() for ln in open(GOLDEN) if ln.strip() and ln[0] != "#"]
-    vals = {r[0]: [int(x) for x in r[1:]] for r in rows}
-    v = sp_cost.volumes(*vals["params"])
-    for key in ("attn_comm", "attn_compute", "mlp_comm", "mlp_compute"):
-        assert [int(x) for x in v[key]] == vals[key] and all(x.denominator == 1 for x in v[key]), key
+def golden_cases():
+    cases, cur = [], None
+    for ln in open(GOLDEN):
+        if not ln.strip() or ln[0] == "#":
+            continue
+        key, *vals = ln.split()
+        if key == "case":
+            cur = {"name": vals[0]}
+            cases.append(cur)
+        else:
+            cur[key] = [int(x) for x in vals]
+    return cases
+
+
+def test_volumes_match_the_hand_evaluated_examples():
+    cases = golden_cases()
+    assert len(cases) == 3
+    for vals in cases:
+        v = sp_cost.volumes(*vals["params"])
+        for key in ("attn_comm", "attn_compute", "mlp_comm", "mlp_compute"):
+            assert [int(x) for x in v[key]] == vals[key] and all(x.denominator == 1 for x in v[key]), (vals["name"], key)
+
+
+def test_time_estimates_match_the_hand_evaluated_examples():
+    """The seconds of every combination, exactly, for stated element size, bandwidth and flop rate (section
+    "Fast Sequence Parallelism for Long-Request Prefill"; communication and computation time are added).
+    Dropping the element size, or swapping bandwidth and flop rate, changes every one of these values;
+    cases B and C differ only in the element size and choose differently."""
+    bests = {}
+    for vals in golden_cases():
+        _, sec, best = sp_cost.select(*vals["params"], *vals["rates"])
+        flat = [sec[0][0], sec[0][1], sec[1][0], sec[1][1]]
+        assert all(x.denominator == 1 for x in flat) and [int(x) for x in flat] == vals["seconds"], vals["name"]
+        assert list(best) == vals["best"], vals["name"]
+        bests[vals["name"]] = best
+    assert bests["B"] != bests["C"]
 
 
 def test_limiting_cases():
@@ -76,6 +106,14 @@ def test_library_matches_the_oracle(lib):
                 assert abs(got["seconds"][a][m] - float(sec[a][m])) <= 1e-12 * float(sec[a][m])
         if flat[1] - flat[0] > 1e-9 * flat[0]:          # a clear winner: the choices must agree
             assert got["best"] == best, args
+
+
+def test_library_matches_the_hand_evaluated_examples(lib):
+    for vals in golden_cases():
+        got = pec.pec_sp_select_strategy(*vals["params"], *vals["rates"])
+        assert [got["seconds"][0][0], got["seconds"][0][1], got["seconds"][1][0], got["seconds"][1][1]] == \
+            [float(x) for x in vals["seconds"]], vals["name"]
+        assert list(got["best"]) == vals["best"], vals["name"]
 
 
 def test_library_rejects_bad_models(lib):
