@@ -7,7 +7,7 @@ order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen|decode_512k|ulysses_layout]
-                  [--sp-mode fused|separate|single] [--variant N] [--share] [--no-cpu-baseline]
+                  [--sp-mode fused|separate|single] [--simple-kernel] [--share] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3_gqa_128k")
     ap.add_argument("--sp-mode", default="fused", choices=["fused", "separate", "single"])
-    ap.add_argument("--variant", type=int, default=None)
+    ap.add_argument("--simple-kernel", action="store_true", help="time the plain cross-check kernel instead of the default")
     ap.add_argument("--share", action="store_true",
                     help="time one GPU's share only: the last ring member's prefill (its query segment against all KV segments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -74,11 +74,9 @@ def main():
     pec.lib()  # fails loudly when the HIP library has not been built
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    if args.variant is not None:
-        pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, args.variant)
-    mode = {"fused": pec.PEC_SP_FUSED_MERGE, "separate": pec.PEC_SP_SEPARATE_MERGE,
-            "single": pec.PEC_SP_SINGLE_LAUNCH}[args.sp_mode]
-    pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
+    mode = {"fused": 0, "separate": pec.PEC_FLAG_SP_SEPARATE_MERGE, "single": pec.PEC_FLAG_SP_SINGLE_LAUNCH}[args.sp_mode]
+    args.kernel_flag = pec.PEC_FLAG_SIMPLE_KERNEL if args.simple_kernel else 0
+    args.flags = mode | args.kernel_flag
 
     if args.workload == "c4_varlen":
         return bench_varlen(args, torch, np, pec, synth, dev)
@@ -101,12 +99,12 @@ def main():
                 for r in range(P) for c in range(r + 1))
     assert pairs == S * (S + 1) // 2
     flops = FLOP_PER_PAIR * Hq * pairs
-    launches = P * (P + 1) // 2 if mode != pec.PEC_SP_SINGLE_LAUNCH else P
+    launches = P * (P + 1) // 2 if mode != pec.PEC_FLAG_SP_SINGLE_LAUNCH else P
 
     def step():
         for r in range(P):
             lo = r * C
-            pec.pec_sp_prefill(q[lo:lo + C], k, v, lo, C, True, out=out[lo:lo + C], lse=lse[r], workspace=ws)
+            pec.pec_sp_prefill(q[lo:lo + C], k, v, lo, C, True, out=out[lo:lo + C], lse=lse[r], workspace=ws, flags=args.flags)
 
     for _ in range(args.warmup):
         step()
@@ -129,7 +127,7 @@ def main():
     achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)], "launches_per_step": launches,
+                "kernel": pec.KERNEL_NAMES[args.kernel_flag], "launches_per_step": launches,
                 "avg_launch_ms": round(avg_launch_ms, 4), "flop_per_launch_avg": flops / launches}
 
     result = {
@@ -140,7 +138,7 @@ def main():
         "config": {"workload": "%s: causal prefill, %d q heads / %d kv heads, d 128, seq %d as %d segments of %d, "
                                "full ring sweep with LSE merge (%s)" % (w.name, Hq, Hkv, S, P, C, args.sp_mode),
                    "seq_len": S, "chunk": C, "n_q_heads": Hq, "n_kv_heads": Hkv, "sp_mode": args.sp_mode,
-                   "kernel_variant": pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)},
+                   "kernel": pec.KERNEL_NAMES[args.kernel_flag]},
         "tokens_per_s": round(S / (ms_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "causal_useful_tflop_per_step": round(flops / 1e12, 3),
@@ -164,10 +162,10 @@ def bench_share(args, torch, pec, synth, dev, w, mode):
     ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C)), dtype=torch.uint8, device=dev)
     lo = S - C
     flops = FLOP_PER_PAIR * Hq * synth.visible_pairs(C, S, lo, 0, True)
-    launches = P if mode != pec.PEC_SP_SINGLE_LAUNCH else 1
+    launches = P if mode != pec.PEC_FLAG_SP_SINGLE_LAUNCH else 1
 
     def step():
-        pec.pec_sp_prefill(q, k, v, lo, C, True, out=out, lse=lse, workspace=ws)
+        pec.pec_sp_prefill(q, k, v, lo, C, True, out=out, lse=lse, workspace=ws, flags=args.flags)
 
     for _ in range(args.warmup):
         step()
@@ -195,7 +193,7 @@ def bench_share(args, torch, pec, synth, dev, w, mode):
         "causal_useful_tflop_per_step": round(flops / 1e12, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                     "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)],
+                     "kernel": pec.KERNEL_NAMES[args.kernel_flag],
                      "launches_per_step": launches, "avg_launch_ms": round(avg_launch_ms, 4)},
     }
     print(json.dumps(result), flush=True)
@@ -248,7 +246,7 @@ def bench_varlen(args, torch, np, pec, synth, dev):
     max_len = int(lengths.max())
 
     def step():
-        pec.pec_attn_varlen(q, k, v, cud, max_len, True, out=out, lse=lse, workspace=ws)
+        pec.pec_attn_varlen(q, k, v, cud, max_len, True, out=out, lse=lse, workspace=ws, flags=args.kernel_flag)
 
     for _ in range(args.warmup):
         step()
@@ -275,7 +273,7 @@ def bench_varlen(args, torch, np, pec, synth, dev):
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                     "kernel": pec.KERNEL_NAMES[pec.pec_get_option(pec.PEC_OPT_KERNEL_VARIANT)]},
+                     "kernel": pec.KERNEL_NAMES[args.kernel_flag]},
     }
     print(json.dumps(result), flush=True)
     return 0
@@ -325,7 +323,7 @@ def bench_decode(args, torch, np, pec, synth, dev):
     HBM-bound: K and V are read once."""
     Hq, Hkv, sk = 64, 8, 524288
     q, k, v = synth.qkv(1005, 1, sk, Hq, Hkv, device=dev)
-    shp = pec.PecShape(Hq, Hkv, 128, 1, 0.0)
+    shp = pec.PecShape(Hq, Hkv, 128, 1, 0.0, 0)
     n_splits = args.decode_splits or int(pec.lib().pec_decode_default_splits(ctypes.byref(shp), sk))   # key ranges per KV head
     out = torch.empty((1, Hq, 128), dtype=torch.float32, device=dev)
     lse = torch.empty((Hq,), dtype=torch.float32, device=dev)

@@ -5,8 +5,9 @@
  * C ABI: plain pointers and sizes only.  Unless said otherwise every pointer is a
  * DEVICE pointer owned by the caller, 16-byte aligned, and every call is
  * asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default
- * stream).  The library keeps no state between calls apart from the tuning
- * options below, allocates no device memory, and never synchronises the device.
+ * stream).  The library keeps no state between calls (every option travels in
+ * pec_shape_t.flags, so concurrent callers cannot disturb each other), allocates
+ * no device memory, and never synchronises the device.
  *
  * Layouts (row-major, contiguous, counts in elements):
  *   q, out  : [tokens, n_q_heads, 128]   bf16 (out: bf16 or fp32, see out_dtype)
@@ -53,7 +54,18 @@ typedef struct {
     int32_t out_dtype;  /* dtype of `out` / `o_acc` / `o_part`: PEC_BF16 (final) or PEC_F32 (partials kept
                            exact across merges) */
     float scale;        /* multiplies q.k; 0 selects 1/sqrt(head_dim) (Eq. 2) */
+    uint32_t flags;     /* PEC_FLAG_* or-ed together; 0 = defaults */
 } pec_shape_t;
+
+/* Per-call options (pec_shape_t.flags). */
+enum {
+    PEC_FLAG_SIMPLE_KERNEL = 1u,     /* run the plain, unpipelined attention kernel (exact running maximum, no
+                                        persistence) instead of the default one: a cross-check, several times slower */
+    PEC_FLAG_SP_SEPARATE_MERGE = 2u, /* pec_sp_prefill: pec_attn_chunk -> fp32 partial -> pec_attn_merge per ring step,
+                                        instead of the default merge fused into the next step's kernel */
+    PEC_FLAG_SP_SINGLE_LAUNCH = 4u   /* pec_sp_prefill: one launch sweeping all segments with the running state in
+                                        registers (no point between segments where a scheduler could stop) */
+};
 
 /*
  * One ring step: attention of a local query segment against ONE key/value
@@ -101,7 +113,9 @@ int pec_finalize(const pec_shape_t* shape, const float* o_f32, void* o_bf16, int
  * (r - t) mod P for step t with r = q_off / chunk; under the causal mask segments
  * wholly in the future are skipped.  Each step is a separate kernel launch, so a
  * scheduler can stop between two steps (section "Preemption of Long-Request
- * Prefill").  How the partials are combined is chosen by PEC_OPT_SP_MODE.
+ * Prefill").  By default step t > 0 folds its segment into the running fp32 pair
+ * inside the kernel (pec_attn_chunk_merge); PEC_FLAG_SP_SEPARATE_MERGE and
+ * PEC_FLAG_SP_SINGLE_LAUNCH select the two other ways of combining the partials.
  *   out [s_q, Hq, 128] in shape->out_dtype, lse [Hq, s_q].
  * workspace: device scratch of at least pec_sp_workspace_bytes() bytes, 16-byte
  * aligned; contents undefined on return.
@@ -122,7 +136,7 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  *   order, each exactly once; anything may run on the GPU, and the state may be copied away and
  *   back, between two steps.  If out_final is not NULL on the last step the result is written
  *   there in shape->out_dtype (and o_acc is then left unchanged); lse_acc always ends as the LSE.
- * Issuing all steps back to back is what pec_sp_prefill does in PEC_SP_FUSED_MERGE mode.
+ * Issuing all steps back to back is what pec_sp_prefill does by default.
  */
 int64_t pec_sp_prefill_num_steps(const pec_shape_t* shape, int64_t s_q, int64_t q_off, int64_t s_kv,
                                  int64_t chunk, int causal);
@@ -137,7 +151,11 @@ int pec_sp_prefill_step(const pec_shape_t* shape, const void* q, const void* k, 
  * q/k/v/out, attends only to itself, positions restart at 0.
  *   cu_seqlens: DEVICE int32 [batch + 1], non-decreasing, cu_seqlens[0] == 0,
  *               cu_seqlens[batch] == total_tokens (not checked; otherwise undefined).
- *   max_seqlen: upper bound on any sequence length (host value).
+ *               Entries are clamped into [0, total_tokens] and made non-decreasing on the
+ *               device, so malformed values can misplace results but never index out of bounds.
+ *   max_seqlen: the caller's bound on the sequence lengths (host value); a HINT only -- the work
+ *               list is sized from total_tokens, so a sequence longer than max_seqlen is still
+ *               processed in full, never cut short.
  *   lse [Hq, total_tokens].  Zero-length sequences are legal.
  * workspace: at least pec_varlen_workspace_bytes() bytes (the device-built work list).
  */
@@ -211,32 +229,6 @@ typedef struct {
 } pec_sp_choice_t;
 
 int pec_sp_select_strategy(const pec_sp_model_t* model, pec_sp_choice_t* choice);
-
-/* Tuning knobs; process-wide, not thread-safe against concurrent calls. */
-enum {
-    PEC_OPT_KERNEL_VARIANT = 0, /* see PEC_VARIANT_* */
-    PEC_OPT_SP_MODE = 1         /* see PEC_SP_* */
-};
-enum {
-    PEC_VARIANT_W4_Q64 = 0,      /* register-staged tiles: 4 wavefronts x 64 query rows */
-    PEC_VARIANT_W8_Q32 = 1,      /* register-staged tiles: 8 wavefronts x 32 query rows */
-    PEC_VARIANT_W4_Q64_NOTR = 2, /* as 0 but V operands gathered with scalar LDS reads (slow; cross-check) */
-    PEC_VARIANT_DMA_W8_Q32 = 3,  /* direct global->LDS tiles: 8 wavefronts x 32 query rows */
-    PEC_VARIANT_DMA_W4_Q32 = 4,  /* direct global->LDS tiles: 4 wavefronts x 32 rows, 128-row workgroups */
-    PEC_VARIANT_DMA_W4_Q64 = 5,  /* direct global->LDS tiles: 4 wavefronts x 64 query rows */
-    PEC_VARIANT_PINGPONG = 6,    /* 8 wavefronts in two groups half a tile apart: one feeds the matrix pipe
-                                    while the other does softmax (groups = wavefronts 0-3 / 4-7) */
-    PEC_VARIANT_PINGPONG_ADJ = 7,/* same, groups = even / odd wavefronts */
-    PEC_VARIANT_INTERLEAVED = 8  /* 8 wavefronts, each software-pipelined: MFMAs of tiles j-1 / j+1 issued
-                                    round-robin with the softmax of tile j (default) */
-};
-enum {
-    PEC_SP_FUSED_MERGE = 0,   /* one pec_attn_chunk_merge launch per ring step (default) */
-    PEC_SP_SEPARATE_MERGE = 1,/* pec_attn_chunk -> fp32 partial -> pec_attn_merge per ring step */
-    PEC_SP_SINGLE_LAUNCH = 2  /* one launch sweeping all segments with the running state in registers */
-};
-int pec_set_option(int option, int value);
-int pec_get_option(int option);
 
 const char* pec_status_string(int status);
 

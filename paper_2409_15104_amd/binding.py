@@ -16,27 +16,19 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpec_attn.so")
 
 PEC_BF16, PEC_F32 = 0, 1
-PEC_OPT_KERNEL_VARIANT, PEC_OPT_SP_MODE = 0, 1
-PEC_VARIANT_W4_Q64, PEC_VARIANT_W8_Q32, PEC_VARIANT_W4_Q64_NOTR = 0, 1, 2
-PEC_VARIANT_DMA_W8_Q32, PEC_VARIANT_DMA_W4_Q32, PEC_VARIANT_DMA_W4_Q64 = 3, 4, 5
-PEC_VARIANT_PINGPONG, PEC_VARIANT_PINGPONG_ADJ, PEC_VARIANT_INTERLEAVED = 6, 7, 8
-KERNEL_NAMES = {0: "pec::fwd_kernel<2, 4, true>", 1: "pec::fwd_kernel<1, 8, true>", 2: "pec::fwd_kernel<2, 4, false>",
-                3: "pec::fwd_dma_kernel<1, 8>", 4: "pec::fwd_dma_kernel<1, 4>", 5: "pec::fwd_dma_kernel<2, 4>",
-                6: "pec::fwd_pp_kernel<true>", 7: "pec::fwd_pp_kernel<false>", 8: "pec::fwd_il_kernel"}
-PEC_VARIANT_DEFAULT = PEC_VARIANT_INTERLEAVED
-PEC_SP_FUSED_MERGE, PEC_SP_SEPARATE_MERGE, PEC_SP_SINGLE_LAUNCH = 0, 1, 2
+PEC_FLAG_SIMPLE_KERNEL, PEC_FLAG_SP_SEPARATE_MERGE, PEC_FLAG_SP_SINGLE_LAUNCH = 1, 2, 4
+KERNEL_NAMES = {0: "pec::fwd_il_kernel", PEC_FLAG_SIMPLE_KERNEL: "pec::fwd_simple_kernel"}
 
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
     "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_set_option",
-    "pec_get_option", "pec_status_string",
+    "pec_decode_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
 )
 
 
 class PecShape(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float), ("flags", ctypes.c_uint32)]
 
 
 class PecSpModel(ctypes.Structure):
@@ -91,13 +83,11 @@ def lib() -> ctypes.CDLL:
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
-        L.pec_set_option.argtypes = [ci, ci]
-        L.pec_get_option.argtypes = [ci]
         L.pec_status_string.argtypes = [ci]
         L.pec_status_string.restype = ctypes.c_char_p
         for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
                      "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy",
-                     "pec_attn_varlen", "pec_set_option", "pec_get_option"):
+                     "pec_attn_varlen"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -112,9 +102,9 @@ def _check(fn: str, status: int) -> None:
         raise PecError(fn, status)
 
 
-def _shape(q: torch.Tensor, k: torch.Tensor, out_dtype, scale: float) -> PecShape:
+def _shape(q: torch.Tensor, k: torch.Tensor, out_dtype, scale: float, flags: int = 0) -> PecShape:
     return PecShape(q.shape[1], k.shape[1], q.shape[2], PEC_F32 if out_dtype == torch.float32 else PEC_BF16,
-                    float(scale))
+                    float(scale), int(flags))
 
 
 def _ptr(t):
@@ -131,16 +121,8 @@ def _require(t: torch.Tensor, dtype, name: str):
         raise ValueError("%s must be a contiguous %s tensor on the GPU" % (name, dtype))
 
 
-def pec_set_option(option: int, value: int) -> None:
-    _check("pec_set_option", lib().pec_set_option(int(option), int(value)))
-
-
-def pec_get_option(option: int) -> int:
-    return int(lib().pec_get_option(int(option)))
-
-
 def pec_attn_chunk(q, k, v, q_off: int, kv_off: int, causal: bool = True, out_dtype=torch.bfloat16,
-                   scale: float = 0.0, out=None, lse=None, stream=None):
+                   scale: float = 0.0, flags: int = 0, out=None, lse=None, stream=None):
     """q [sq,Hq,128], k/v [sk,Hkv,128] bf16 -> (out [sq,Hq,128] out_dtype, lse [Hq,sq] fp32)."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
@@ -152,7 +134,7 @@ def pec_attn_chunk(q, k, v, q_off: int, kv_off: int, causal: bool = True, out_dt
         lse = torch.empty((hq, sq), dtype=torch.float32, device=q.device)
     _require(out, out_dtype, "out")
     _require(lse, torch.float32, "lse")
-    shp = _shape(q, k, out_dtype, scale)
+    shp = _shape(q, k, out_dtype, scale, flags)
     _check("pec_attn_chunk", lib().pec_attn_chunk(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), sq, sk, int(q_off),
                                                   int(kv_off), int(bool(causal)), _ptr(out), _ptr(lse),
                                                   _stream(stream)))
@@ -160,14 +142,14 @@ def pec_attn_chunk(q, k, v, q_off: int, kv_off: int, causal: bool = True, out_dt
 
 
 def pec_attn_chunk_merge(q, k, v, q_off: int, kv_off: int, o_acc, lse_acc, causal: bool = True, out_final=None,
-                         scale: float = 0.0, stream=None):
+                         scale: float = 0.0, flags: int = 0, stream=None):
     """Fold one KV segment into the running fp32 (o_acc, lse_acc) in place; optionally also emit out_final."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
     _require(o_acc, torch.float32, "o_acc")
     _require(lse_acc, torch.float32, "lse_acc")
     out_dtype = out_final.dtype if out_final is not None else torch.bfloat16
-    shp = _shape(q, k, out_dtype, scale)
+    shp = _shape(q, k, out_dtype, scale, flags)
     _check("pec_attn_chunk_merge",
            lib().pec_attn_chunk_merge(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), q.shape[0], k.shape[0], int(q_off),
                                       int(kv_off), int(bool(causal)), _ptr(o_acc), _ptr(lse_acc), _ptr(out_final),
@@ -184,7 +166,7 @@ def pec_attn_merge(o_acc, lse_acc, o_part, lse_part, stream=None):
     _require(lse_acc, torch.float32, "lse_acc")
     _require(lse_part, torch.float32, "lse_part")
     sq, hq, d = o_acc.shape
-    shp = PecShape(hq, hq, d, PEC_F32 if o_acc.dtype == torch.float32 else PEC_BF16, 0.0)
+    shp = PecShape(hq, hq, d, PEC_F32 if o_acc.dtype == torch.float32 else PEC_BF16, 0.0, 0)
     _check("pec_attn_merge", lib().pec_attn_merge(ctypes.byref(shp), _ptr(o_acc), _ptr(lse_acc), _ptr(o_part),
                                                   _ptr(lse_part), sq, _stream(stream)))
     return o_acc, lse_acc
@@ -195,18 +177,18 @@ def pec_finalize(o_f32, o_bf16=None, stream=None):
     sq, hq, d = o_f32.shape
     if o_bf16 is None:
         o_bf16 = torch.empty((sq, hq, d), dtype=torch.bfloat16, device=o_f32.device)
-    shp = PecShape(hq, hq, d, PEC_BF16, 0.0)
+    shp = PecShape(hq, hq, d, PEC_BF16, 0.0, 0)
     _check("pec_finalize", lib().pec_finalize(ctypes.byref(shp), _ptr(o_f32), _ptr(o_bf16), sq, _stream(stream)))
     return o_bf16
 
 
 def pec_sp_workspace_bytes(n_q_heads: int, n_kv_heads: int, s_q: int) -> int:
-    shp = PecShape(n_q_heads, n_kv_heads, 128, PEC_BF16, 0.0)
+    shp = PecShape(n_q_heads, n_kv_heads, 128, PEC_BF16, 0.0, 0)
     return int(lib().pec_sp_workspace_bytes(ctypes.byref(shp), int(s_q)))
 
 
 def pec_sp_prefill(q, k, v, q_off: int, chunk: int, causal: bool = True, out_dtype=torch.bfloat16,
-                   scale: float = 0.0, out=None, lse=None, workspace=None, stream=None):
+                   scale: float = 0.0, flags: int = 0, out=None, lse=None, workspace=None, stream=None):
     """One ring member's prefill: q [s_q,Hq,128] at q_off vs k/v [s_kv,Hkv,128] in segments of `chunk`."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
@@ -216,7 +198,7 @@ def pec_sp_prefill(q, k, v, q_off: int, chunk: int, causal: bool = True, out_dty
         out = torch.empty((s_q, hq, d), dtype=out_dtype, device=q.device)
     if lse is None:
         lse = torch.empty((hq, s_q), dtype=torch.float32, device=q.device)
-    shp = _shape(q, k, out_dtype, scale)
+    shp = _shape(q, k, out_dtype, scale, flags)
     if workspace is None:
         workspace = torch.empty(max(16, int(lib().pec_sp_workspace_bytes(ctypes.byref(shp), s_q))), dtype=torch.uint8,
                                 device=q.device)
@@ -237,14 +219,14 @@ def pec_sp_prefill_num_steps(q, k, q_off: int, chunk: int, causal: bool = True) 
 
 
 def pec_sp_prefill_step(q, k, v, q_off: int, chunk: int, step: int, o_acc, lse_acc, causal: bool = True,
-                        out_final=None, scale: float = 0.0, stream=None):
+                        out_final=None, scale: float = 0.0, flags: int = 0, stream=None):
     """Ring step number `step` of the member's prefill, folded into the caller-kept state (o_acc, lse_acc)."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
     _require(o_acc, torch.float32, "o_acc")
     _require(lse_acc, torch.float32, "lse_acc")
     out_dtype = out_final.dtype if out_final is not None else torch.bfloat16
-    shp = _shape(q, k, out_dtype, scale)
+    shp = _shape(q, k, out_dtype, scale, flags)
     _check("pec_sp_prefill_step",
            lib().pec_sp_prefill_step(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), q.shape[0], int(q_off), k.shape[0],
                                      int(chunk), int(bool(causal)), int(step), _ptr(o_acc), _ptr(lse_acc),
@@ -252,7 +234,7 @@ def pec_sp_prefill_step(q, k, v, q_off: int, chunk: int, step: int, o_acc, lse_a
     return o_acc, lse_acc
 
 
-def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scale: float = 0.0, out=None, lse=None,
+def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scale: float = 0.0, flags: int = 0, out=None, lse=None,
                        workspace=None, stream=None):
     """One new token q [1,Hq,128] against a KV-cache shard k/v [sk,Hkv,128] -> (out [1,Hq,128], lse [Hq])."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
@@ -261,7 +243,7 @@ def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scal
         raise ValueError("pec_decode_splitkv takes exactly one query token")
     hq = q.shape[1]
     sk = k.shape[0]
-    shp = _shape(q, k, out_dtype, scale)
+    shp = _shape(q, k, out_dtype, scale, flags)
     if n_splits == 0:
         n_splits = int(lib().pec_decode_default_splits(ctypes.byref(shp), sk))
     if out is None:
@@ -311,7 +293,7 @@ def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:
 
 
 def pec_attn_varlen(q, k, v, cu_seqlens, max_seqlen: int, causal: bool = True, out_dtype=torch.bfloat16,
-                    scale: float = 0.0, out=None, lse=None, workspace=None, stream=None):
+                    scale: float = 0.0, flags: int = 0, out=None, lse=None, workspace=None, stream=None):
     """Packed batch: q [T,Hq,128], k/v [T,Hkv,128], cu_seqlens int32 [B+1] on the GPU."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
@@ -324,7 +306,7 @@ def pec_attn_varlen(q, k, v, cu_seqlens, max_seqlen: int, causal: bool = True, o
         lse = torch.empty((hq, total), dtype=torch.float32, device=q.device)
     if workspace is None:
         workspace = torch.empty(max(16, pec_varlen_workspace_bytes(batch, total)), dtype=torch.uint8, device=q.device)
-    shp = _shape(q, k, out_dtype, scale)
+    shp = _shape(q, k, out_dtype, scale, flags)
     _check("pec_attn_varlen",
            lib().pec_attn_varlen(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), batch, total,
                                  int(max_seqlen), int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace),

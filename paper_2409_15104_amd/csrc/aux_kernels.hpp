@@ -5,7 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "fwd_kernel.hpp"
+#include "common.hpp"
 
 namespace pec {
 
@@ -137,43 +137,78 @@ __global__ __launch_bounds__(256) void ulysses_layout_kernel(const u32x4* __rest
     }
 }
 
-// Work list for a packed batch: one item per (sequence, query tile), ordered by
-// descending query-tile index so the longest causal rows start first.  Single
-// workgroup; `bucket` and `cursor` are int32[max_qtiles] scratch.
-__global__ __launch_bounds__(1024) void build_worklist_kernel(const int32_t* __restrict__ cu, int batch, int bm,
-                                                              int max_qtiles, int capacity,
+// Exclusive suffix sum in place over a[0..n), by one workgroup of 1024 threads: a[t] <- sum of the old
+// a[t'] for t' > t.  Returns the sum of all old elements.  `red` is int32[1024] in LDS.
+__device__ inline int block_suffix_sum_1024(int32_t* a, int n, int32_t* red) {
+    const int tid = threadIdx.x;
+    const int chunk = (n + 1023) / 1024;
+    const int lo = min(n, tid * chunk), hi = min(n, lo + chunk);
+    int mine = 0;
+    for (int t = lo; t < hi; ++t) mine += a[t];
+    red[tid] = mine;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {   // inclusive suffix scan of the per-thread sums
+        const int add = tid + off < 1024 ? red[tid + off] : 0;
+        __syncthreads();
+        red[tid] += add;
+        __syncthreads();
+    }
+    const int total = red[0];
+    int run = red[tid] - mine;                   // everything owned by later threads
+    __syncthreads();
+    for (int t = hi - 1; t >= lo; --t) {
+        const int x = a[t];
+        a[t] = run;
+        run += x;
+    }
+    __syncthreads();
+    return total;
+}
+
+// Work list for a packed batch: one item per (sequence, query tile), ordered by descending
+// query-tile index so that the longest causal rows start first.  Single workgroup of 1024 threads;
+// `bucket` (int32[cap + 1]) and `cursor` (int32[cap]) are scratch, cap >= total_tokens / bm + 1.
+// Sequence bounds are clamped into [0, total_tokens] exactly as the attention kernel clamps them, so
+// no sequence can have more than total_tokens / bm + 1 tiles and none is ever cut short.
+__global__ __launch_bounds__(1024) void build_worklist_kernel(const int32_t* __restrict__ cu, int batch,
+                                                              int total_tokens, int bm, int capacity,
                                                               WorkItem* __restrict__ work,
                                                               int32_t* __restrict__ n_work,
                                                               int32_t* __restrict__ bucket,
                                                               int32_t* __restrict__ cursor) {
+    __shared__ int32_t red[1024];
     const int tid = threadIdx.x;
-    for (int t = tid; t < max_qtiles; t += blockDim.x) {
-        bucket[t] = 0;
-        cursor[t] = 0;
-    }
+    auto tiles_of = [&](int b) {
+        const int b0 = min(max(cu[b], 0), total_tokens);
+        const int b1 = min(max(cu[b + 1], b0), total_tokens);
+        return (b1 - b0 + bm - 1) / bm;
+    };
+    // largest tile count of any sequence: only that many buckets are touched
+    int mx = 0;
+    for (int b = tid; b < batch; b += 1024) mx = max(mx, tiles_of(b));
+    red[tid] = mx;
     __syncthreads();
-    for (int b = tid; b < batch; b += blockDim.x) {
-        const int len = cu[b + 1] - cu[b];
-        const int nq = min(max_qtiles, (len + bm - 1) / bm);
-        for (int t = 0; t < nq; ++t) atomicAdd(&bucket[t], 1);
+    for (int off = 512; off > 0; off >>= 1) {
+        if (tid < off) red[tid] = max(red[tid], red[tid + off]);
+        __syncthreads();
     }
+    const int n_t = red[0];
     __syncthreads();
-    if (tid == 0) {
-        int run = 0;   // bucket[t] becomes the list position of the first item with tile index t
-        for (int t = max_qtiles - 1; t >= 0; --t) {
-            const int c = bucket[t];
-            bucket[t] = run;
-            run += c;
-        }
-        *n_work = min(run, capacity);
-    }
+    for (int t = tid; t <= n_t; t += 1024) bucket[t] = 0;
+    for (int t = tid; t < n_t; t += 1024) cursor[t] = 0;
     __syncthreads();
-    for (int b = tid; b < batch; b += blockDim.x) {
-        const int len = cu[b + 1] - cu[b];
-        const int nq = min(max_qtiles, (len + bm - 1) / bm);
-        for (int t = 0; t < nq; ++t) {
+    for (int b = tid; b < batch; b += 1024) atomicAdd(&bucket[tiles_of(b)], 1);   // histogram of tile counts
+    __syncthreads();
+    block_suffix_sum_1024(bucket, n_t + 1, red);                   // bucket[t] = sequences with more than t tiles
+    const int total = block_suffix_sum_1024(bucket, n_t, red);     // bucket[t] = list position of the first item of tile t
+    if (tid == 0) *n_work = min(total, capacity);
+    // placement: one wavefront per sequence, one lane per tile
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int b = wave; b < batch; b += 16) {
+        const int nq = tiles_of(b);
+        for (int t = lane; t < nq; t += 64) {
             const int pos = bucket[t] + atomicAdd(&cursor[t], 1);
-            if (pos < capacity) {   // only a malformed cu_seqlens can overflow the list
+            if (pos < capacity) {   // cannot overflow: capacity bounds the item count of any clamped cu_seqlens
                 work[pos].seq = b;
                 work[pos].qtile = t;
             }

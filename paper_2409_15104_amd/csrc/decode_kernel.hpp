@@ -15,8 +15,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "fwd_kernel.hpp"
-#include "fwd_kernel_dma.hpp"   // bf16x2 / f32x2
+#include "common.hpp"
 
 namespace pec {
 
@@ -84,7 +83,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const DecodePara
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                      :
                      : "v"(voff), "s"(sbase), "s"(lds_addr)
-                     : "memory");
+                     : "memory", "m0");
     };
     auto issue_tile = [&](int tile) {
         if (tile >= n_tiles) return;

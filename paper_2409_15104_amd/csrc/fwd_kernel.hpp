@@ -1,94 +1,23 @@
-// Blockwise attention forward kernel for gfx950 (CDNA4): S^T = K Q^T and O^T = V^T P^T
-// on v_mfma_f32_32x32x16_bf16, online softmax in registers (Eq. 2-3 of the paper,
-// evaluated tile by tile with a running row maximum and denominator).
-//
-// Work decomposition
-//   workgroup : BM = NWAVES*NT*32 query rows of one query head; K/V tiles of BN = 64
-//               keys are staged through LDS (double buffered) and shared by all waves.
-//   wave      : NT sub-tiles of 32 query rows.  Scores are computed TRANSPOSED
-//               (keys along the MFMA M dimension, queries along N) so that each lane
-//               owns one query column: row max / row sum are in-lane reductions plus
-//               one exchange between the two lane halves, and the running rescale of
-//               O is a per-lane scalar.
-//   MFMA 32x32x16 operand layout (lane l, l32 = l % 32, hl = l / 32):
-//     A[M=32][K=16]: lane holds row l32, k-slots 8*hl .. 8*hl+7
-//     B[K=16][N=32]: lane holds column l32, k-slots 8*hl .. 8*hl+7
-//     C[M=32][N=32]: lane holds column l32, rows 8*(r/4) + 4*hl + r%4 for register r
-//   The contraction only needs A and B to agree on which index sits in which
-//   k-slot, so P (taken straight from the score registers) fixes the key order of
-//   the V^T operand: slots 0..3 <- keys 16*t2 + 4*hl + 0..3, slots 4..7 <- +8.
-//
-// LDS layout: a tile is 64 rows (keys) of 256 B (128 bf16).  K rows are XOR-swizzled
-// at 16 B granularity (chunk c -> c ^ (key & 15)) for conflict-free b128 operand
-// reads; V rows at 64 B granularity (segment s -> s ^ (key & 3)) for the transposing
-// ds_read_b64_tr_b16 reads that deliver 4 consecutive keys of one head-dim column.
+// Plain blockwise attention forward kernel for gfx950 (CDNA4), kept as the cross-check of the
+// pipelined kernel in fwd_kernel_il.hpp (selected per call with PEC_FLAG_SIMPLE_KERNEL): the same
+// mathematics -- S^T = K Q^T and O^T = V^T P^T on v_mfma_f32_32x32x16_bf16, online softmax in
+// registers (Eq. 2-3 of the paper evaluated tile by tile with the exact running row maximum and
+// denominator) -- in the most direct organisation: 8 wavefronts x 32 query rows per workgroup, K/V
+// tiles of 64 keys staged global -> registers -> LDS (double buffered), one workgroup per (query
+// tile, head), no persistence, no lazy softmax reference, no fused split-KV mode.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "common.hpp"
+
 namespace pec {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kSimpleWaves = 8;
+constexpr int kSimpleBM = kSimpleWaves * 32;   // query rows per workgroup
 
-constexpr int kHeadDim = 128;
-constexpr int kBN = 64;               // keys per LDS tile
-constexpr int kRowBytes = 256;        // one key row of 128 bf16
-constexpr int kTileBytes = kBN * kRowBytes;
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-struct WorkItem {   // one (sequence, query tile) of a packed batch
-    int32_t seq;
-    int32_t qtile;
-};
-
-struct FwdParams {
-    const __bf16* q;
-    const __bf16* k;
-    const __bf16* v;
-    void* out;              // [tokens, Hq, 128] bf16 or fp32 (may be null when only acc_out is wanted)
-    float* lse;             // [Hq, lse_stride]
-    const float* acc_in;    // running O (fp32, normalised) to continue from, or null
-    const float* lse_in;    // running LSE matching acc_in
-    float* acc_out;         // fp32 copy of the result (running state), or null
-    int64_t lse_stride;     // tokens per head row in lse arrays
-    int32_t sq, sk;         // dense mode: rows / keys of this call
-    int32_t delta;          // q_off - kv_off, clamped to [-sq-1, sk]
-    int32_t causal;
-    int32_t n_q_heads, n_kv_heads, group;
-    int32_t n_items;        // query tiles (dense) or work-list capacity (varlen)
-    int32_t out_f32;
-    float scale_log2;       // scale * log2(e)
-    // varlen mode (cu_seqlens != null): work list built on the device
-    const int32_t* cu_seqlens;
-    const WorkItem* work;
-    const int32_t* n_work;  // number of valid work items
-    int32_t total_tokens;   // rows of the packed arrays (bounds every index taken from cu_seqlens)
-    // split-KV mode (kv_split_len > 0; fwd_il_kernel only): work item = key range
-    // [item * kv_split_len, ...), partial results go to out / lse + item * split_*_stride
-    int32_t kv_split_len;
-    int64_t split_out_stride, split_lse_stride;   // elements
-    // element strides of q / out / acc between rows and between heads (0 = the packed
-    // [tokens, n_q_heads, 128] layout; fwd_il_kernel only)
-    int64_t q_row_stride, q_head_stride;
-};
-
-__device__ __forceinline__ uint32_t k_lds_off(int key, int chunk16) {
-    return (uint32_t)(key * kRowBytes + ((chunk16 ^ (key & 15)) << 4));
-}
-__device__ __forceinline__ uint32_t v_lds_off(int key, int byte_in_row) {
-    const int seg = byte_in_row >> 6;
-    return (uint32_t)(key * kRowBytes + (((seg ^ (key & 3)) << 6) | (byte_in_row & 63)));
-}
-
-template <int NT, int NWAVES, bool USE_TR>
-__global__ __launch_bounds__(NWAVES * 64) void fwd_kernel(const FwdParams p) {
+__global__ __launch_bounds__(kSimpleWaves * 64) void fwd_simple_kernel(const FwdParams p) {
+    constexpr int NT = 1, NWAVES = kSimpleWaves;
     constexpr int NTHREADS = NWAVES * 64;
     constexpr int BM = NWAVES * NT * 32;
     constexpr int LOADS = (kBN * 16) / NTHREADS;  // 16-byte chunks per thread per tile
@@ -332,25 +261,16 @@ __global__ __launch_bounds__(NWAVES * 64) void fwd_kernel(const FwdParams p) {
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
                     bf16x8 vf;
-                    if constexpr (USE_TR) {
-                        // 16 lanes cooperate: lane i of a group supplies key kb0 + i/4, columns 4*(i%4)..+3
-                        // of the group's 16 columns and receives 4 consecutive keys of column i.
-                        const int gi = l32 & 15, gg = l32 >> 4;
-                        const int col_byte = dt * 64 + gg * 32 + (gi & 3) * 8;
-                        const int ka = kb0 + (gi >> 2);
-                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                            (__attribute__((address_space(3))) bf16x4*)(vb + v_lds_off(ka, col_byte)));
-                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                            (__attribute__((address_space(3))) bf16x4*)(vb + v_lds_off(ka + 8, col_byte)));
-                        vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    } else {
-                        const int col_byte = (dt * 32 + l32) * 2;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const int key = kb0 + (e & 3) + ((e >> 2) << 3);
-                            vf[e] = *reinterpret_cast<const __bf16*>(vb + v_lds_off(key, col_byte));
-                        }
-                    }
+                    // 16 lanes cooperate: lane i of a group supplies key kb0 + i/4, columns 4*(i%4)..+3
+                    // of the group's 16 columns and receives 4 consecutive keys of column i.
+                    const int gi = l32 & 15, gg = l32 >> 4;
+                    const int col_byte = dt * 64 + gg * 32 + (gi & 3) * 8;
+                    const int ka = kb0 + (gi >> 2);
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4*)(vb + v_lds_off(ka, col_byte)));
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4*)(vb + v_lds_off(ka + 8, col_byte)));
+                    vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
                         o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][mt][t2], o[dt][nt], 0, 0, 0);

@@ -15,8 +15,11 @@
 // cycles, so only 4 to 5 plain VALU instructions per MFMA are free; every one beyond that costs
 // about 2 cycles, a transcendental about 5.  Hence the softmax reference m is kept lazily
 // (see row_max) and unmasked tiles do without a row maximum (see body).
-// Same MFMA operand layouts, LDS swizzles and direct global->LDS tile loads as
-// fwd_kernel_dma.hpp; 8 wavefronts x 32 query rows; one workgroup barrier per tile.
+// MFMA operand layouts and LDS swizzles as described in common.hpp; K/V tiles go global -> LDS
+// directly (global_load_lds_dwordx4: no staging registers, no ds_write; the XOR swizzles are applied
+// on the global side by choosing which 16-byte chunk each lane fetches, a permutation inside one
+// 256 B row, so the global access stays fully coalesced); 8 wavefronts x 32 query rows; one
+// workgroup barrier per tile.
 //
 // LDS: two stages each for K and V (four arrays; every access names its array because the
 // loop is unrolled by two).  Iteration j, parity
@@ -28,20 +31,23 @@
 
 #include <type_traits>
 
-#include "fwd_kernel.hpp"
-#include "fwd_kernel_dma.hpp"
+#include "common.hpp"
 
 namespace pec {
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
-// The compiler's hazard recogniser does not look inside inline asm, and the hardware does not
-// interlock a VALU read of a register an MFMA is still writing: callers put mfma_settle() between
-// the last MFMA and the first scale_acc_in_place().
-__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15"); }
-__device__ __forceinline__ void scale_acc_in_place(f32x16& x, float a) {
+// In-place rescale of the four O accumulators.  The compiler's hazard recogniser does not look inside
+// inline asm, and the hardware does not interlock a VALU read of a register an MFMA is still writing,
+// so the wait states sit in ONE asm statement that takes all four accumulators as read-write operands:
+// every MFMA that produces them is ordered before it by the data dependence, and nothing can move
+// between the wait and the multiplications that follow it in the same statement sequence.
+__device__ __forceinline__ void scale_acc_in_place(f32x16 (&o)[4], float a) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]));
 #pragma unroll
-    for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x[r]) : "v"(a));
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(o[dt][r]) : "v"(a));
 }
 
 __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
@@ -194,7 +200,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                      :
                      : "v"(voff), "s"(sbase), "s"(lds_addr)
-                     : "memory");
+                     : "memory", "m0");
     };
     auto issue_tile = [&](const unsigned char* base, bool is_v, uint32_t full_off0, int tile, unsigned char* stage) {
         if (tile >= n_tiles) return;
@@ -456,19 +462,13 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                     rs_fast = weights_rs(s_b, p_b);
                 }
                 l_run *= alpha;
-                mfma_settle();
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha);
+                scale_acc_in_place(o, alpha);
                 alpha = 1.f;        // nothing pending for tile j + 1: its reference is the current one
                 m_use = m_run;
             }
             l_run += rs_fast;
         } else {
-            if (__any(alpha_j != 1.f)) {
-                mfma_settle();
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) scale_acc_in_place(o[dt], alpha_j);
-            }
+            if (__any(alpha_j != 1.f)) scale_acc_in_place(o, alpha_j);
         }
         end_of_iteration();
     };

@@ -10,34 +10,15 @@
 #include <cstdlib>
 
 #include "aux_kernels.hpp"
+#include "common.hpp"
 #include "decode_kernel.hpp"
 #include "fwd_kernel.hpp"
-#include "fwd_kernel_dma.hpp"
 #include "fwd_kernel_il.hpp"
-#include "fwd_kernel_pp.hpp"
 
 namespace {
 
 using namespace pec;
 
-// Kernel variants (PEC_VARIANT_*): query rows per workgroup and the launcher.
-typedef void (*launch_fn)(const FwdParams&, unsigned grid, hipStream_t);
-template <int NT, int NWAVES, bool TR>
-void launch_v1(const FwdParams& p, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL((fwd_kernel<NT, NWAVES, TR>), dim3(grid), dim3(NWAVES * 64), 0, st, p);
-}
-template <int NT, int NWAVES>
-void launch_dma(const FwdParams& p, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL((fwd_dma_kernel<NT, NWAVES>), dim3(grid), dim3(NWAVES * 64), 0, st, p);
-}
-template <bool PAIR_STRIDE4>
-void launch_pp(const FwdParams& p, unsigned grid, hipStream_t st) {
-    // 96 KiB of dynamic LDS is above the default limit: raise it once per process
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_pp_kernel<PAIR_STRIDE4>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPpLdsBytes);
-    (void)attr;
-    hipLaunchKernelGGL((fwd_pp_kernel<PAIR_STRIDE4>), dim3(grid), dim3(512), kPpLdsBytes, st, p);
-}
 // Compute units of the current device (cached per device id).
 int compute_units() {
     static int cached[64] = {0};
@@ -50,35 +31,20 @@ int compute_units() {
     }
     return cached[dev];
 }
-// The interleaved kernel is persistent: one workgroup per compute unit (its registers allow no
+// The pipelined kernel is persistent: one workgroup per compute unit (its registers allow no
 // second one), each walking its share of the `grid` logical work items.
 void launch_il(const FwdParams& p, unsigned grid, hipStream_t st) {
     const unsigned per_xcd = grid / 8;
     const unsigned slots = std::max(1u, std::min(per_xcd, (unsigned)compute_units() / 8));
     hipLaunchKernelGGL(fwd_il_kernel, dim3(8 * slots), dim3(512), 0, st, p);
 }
-struct Variant {
-    int bm;
-    launch_fn launch;
-};
-const Variant kVariants[] = {
-    {256, launch_v1<2, 4, true>},   // PEC_VARIANT_W4_Q64
-    {256, launch_v1<1, 8, true>},   // PEC_VARIANT_W8_Q32
-    {256, launch_v1<2, 4, false>},  // PEC_VARIANT_W4_Q64_NOTR
-    {256, launch_dma<1, 8>},        // PEC_VARIANT_DMA_W8_Q32
-    {128, launch_dma<1, 4>},        // PEC_VARIANT_DMA_W4_Q32
-    {256, launch_dma<2, 4>},        // PEC_VARIANT_DMA_W4_Q64
-    {256, launch_pp<true>},         // PEC_VARIANT_PINGPONG
-    {256, launch_pp<false>},        // PEC_VARIANT_PINGPONG_ADJ
-    {256, launch_il},               // PEC_VARIANT_INTERLEAVED
-};
-constexpr int N_VARIANTS = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-int g_variant = PEC_VARIANT_INTERLEAVED;
-int g_sp_mode = PEC_SP_FUSED_MERGE;
+// Both kernels take 256 query rows per workgroup, so work lists and launch geometry do not depend
+// on which one a call selects.
+constexpr int kBM = 256;
+static_assert(kSimpleBM == kBM, "the two kernels must agree on the query tile");
 
 constexpr int64_t kMaxRows = (int64_t)1 << 30;
-constexpr int kMinBM = 128;        // smallest query tile of any variant; bounds work-list sizes
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -87,6 +53,9 @@ int check_shape(const pec_shape_t* s, float* scale_out) {
     if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0) return PEC_ERR_INVALID_ARGUMENT;
     if (s->head_dim != kHeadDim) return PEC_ERR_UNSUPPORTED;
     if (s->out_dtype != PEC_BF16 && s->out_dtype != PEC_F32) return PEC_ERR_UNSUPPORTED;
+    if (s->flags & ~(uint32_t)(PEC_FLAG_SIMPLE_KERNEL | PEC_FLAG_SP_SEPARATE_MERGE | PEC_FLAG_SP_SINGLE_LAUNCH))
+        return PEC_ERR_UNSUPPORTED;
+    if ((s->flags & PEC_FLAG_SP_SEPARATE_MERGE) && (s->flags & PEC_FLAG_SP_SINGLE_LAUNCH)) return PEC_ERR_INVALID_ARGUMENT;
     float scale = s->scale;
     if (scale == 0.f) scale = 1.0f / std::sqrt((float)s->head_dim);
     if (!(scale > 0.f) || !std::isfinite(scale)) return PEC_ERR_INVALID_ARGUMENT;
@@ -94,13 +63,16 @@ int check_shape(const pec_shape_t* s, float* scale_out) {
     return PEC_OK;
 }
 
-int launch_fwd(const FwdParams& p, hipStream_t stream) {
+int launch_fwd(const FwdParams& p, bool simple, hipStream_t stream) {
     const int64_t total = (int64_t)p.n_items * p.n_q_heads;
     if (total <= 0) return PEC_OK;
     const int64_t per_xcd = (total + 7) / 8;
     const int64_t grid = per_xcd * 8;
     if (grid > 0x7fffffffLL) return PEC_ERR_UNSUPPORTED;
-    kVariants[g_variant].launch(p, (unsigned)grid, stream);
+    if (simple)
+        hipLaunchKernelGGL(fwd_simple_kernel, dim3((unsigned)grid), dim3(kSimpleWaves * 64), 0, stream, p);
+    else
+        launch_il(p, (unsigned)grid, stream);
     return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
 }
 
@@ -137,11 +109,10 @@ int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const voi
     p.n_q_heads = shape->n_q_heads;
     p.n_kv_heads = shape->n_kv_heads;
     p.group = shape->n_q_heads / shape->n_kv_heads;
-    const int bm = kVariants[g_variant].bm;
-    p.n_items = (int32_t)((sq + bm - 1) / bm);
+    p.n_items = (int32_t)((sq + kBM - 1) / kBM);
     p.out_f32 = out_f32;
     p.scale_log2 = scale * kLog2e;
-    return launch_fwd(p, static_cast<hipStream_t>(stream));
+    return launch_fwd(p, (shape->flags & PEC_FLAG_SIMPLE_KERNEL) != 0, static_cast<hipStream_t>(stream));
 }
 
 // Ring schedule of one member: step t brings segment (r - t) mod P with r = q_off / chunk (own
@@ -221,7 +192,7 @@ int pec_finalize(const pec_shape_t* shape, const float* o_f32, void* o_bf16, int
 
 size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q) {
     if (!shape || s_q <= 0 || shape->n_q_heads <= 0) return 0;
-    // running fp32 O, one fp32 partial O, one partial LSE (the last two only in PEC_SP_SEPARATE_MERGE)
+    // running fp32 O, one fp32 partial O, one partial LSE (the last two only with PEC_FLAG_SP_SEPARATE_MERGE)
     const size_t o = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
     const size_t l = (((size_t)s_q * shape->n_q_heads * sizeof(float)) + 255) & ~(size_t)255;
     return 2 * o + l;
@@ -242,7 +213,7 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
     const __bf16* kp = static_cast<const __bf16*>(k);
     const __bf16* vp = static_cast<const __bf16*>(v);
 
-    if (g_sp_mode == PEC_SP_SINGLE_LAUNCH || s_kv == 0)
+    if ((shape->flags & PEC_FLAG_SP_SINGLE_LAUNCH) || s_kv == 0)
         return chunk_impl(shape, q, k, v, s_q, s_kv, q_off, 0, causal, out, out_f32, lse, nullptr, nullptr, nullptr, s_q,
                           stream);
 
@@ -259,7 +230,7 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
     const size_t o_bytes = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
     float* o_acc = static_cast<float*>(workspace);
 
-    if (g_sp_mode == PEC_SP_FUSED_MERGE) {
+    if (!(shape->flags & PEC_FLAG_SP_SEPARATE_MERGE)) {
         for (int64_t t = 0; t < n_steps; ++t) {
             const int rc = pec_sp_prefill_step(shape, q, k, v, s_q, q_off, s_kv, chunk, causal, t, o_acc, lse,
                                                t == n_steps - 1 ? out : nullptr, stream);
@@ -268,7 +239,7 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
         return PEC_OK;
     }
 
-    // PEC_SP_SEPARATE_MERGE: fp32 partial of every step through HBM, stand-alone merge kernel
+    // PEC_FLAG_SP_SEPARATE_MERGE: fp32 partial of every step through HBM, stand-alone merge kernel
     float* o_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + o_bytes);
     float* lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * o_bytes);
     pec_shape_t part_shape = *shape;
@@ -496,9 +467,10 @@ int pec_sp_select_strategy(const pec_sp_model_t* m, pec_sp_choice_t* c) {
 
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens) {
     if (batch < 0 || total_tokens < 0) return 0;
-    const size_t cap = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;
+    // every sequence contributes at most len / 256 + 1 items
+    const size_t cap = (size_t)(total_tokens / kBM) + (size_t)batch + 1;
     // work list + counter (padded) + two int32 arrays indexed by query-tile number
-    return cap * sizeof(WorkItem) + 256 + 2 * cap * sizeof(int32_t);
+    return cap * sizeof(WorkItem) + 256 + (2 * cap + 1) * sizeof(int32_t);
 }
 
 int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
@@ -508,27 +480,23 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
     if (int rc = check_shape(shape, &scale)) return rc;
     if (batch < 0 || total_tokens < 0 || max_seqlen < 0) return PEC_ERR_INVALID_ARGUMENT;
     if (total_tokens > kMaxRows) return PEC_ERR_UNSUPPORTED;
-    if (batch == 0 || total_tokens == 0 || max_seqlen == 0) return PEC_OK;
+    if (batch == 0 || total_tokens == 0) return PEC_OK;
     if (!q || !k || !v || !out || !lse || !cu_seqlens) return PEC_ERR_INVALID_ARGUMENT;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace) ||
         (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u))
         return PEC_ERR_MISALIGNED;
     if (!workspace || workspace_bytes < pec_varlen_workspace_bytes(batch, total_tokens)) return PEC_ERR_WORKSPACE;
+    (void)max_seqlen;   // a hint only: the work list is sized from total_tokens, so an understated value costs nothing
 
-    const int64_t max_len = std::min<int64_t>(max_seqlen, total_tokens);
-    const int kBM = kVariants[g_variant].bm;
-    const int max_qtiles = (int)((max_len + kBM - 1) / kBM);
-    // every sequence contributes at most len/BM + 1 items
-    const int64_t cap64 = total_tokens / kBM + batch;
-    const size_t cap_alloc = (size_t)(total_tokens / kMinBM) + (size_t)batch + 1;
-    const int capacity = (int)std::min<int64_t>(cap64, (int64_t)cap_alloc);
+    const size_t cap = (size_t)(total_tokens / kBM) + (size_t)batch + 1;
+    const int capacity = (int)std::min<size_t>(cap, 0x7fffffff);
     char* ws = static_cast<char*>(workspace);
     WorkItem* work = reinterpret_cast<WorkItem*>(ws);
-    int32_t* n_work = reinterpret_cast<int32_t*>(ws + cap_alloc * sizeof(WorkItem));
-    int32_t* bucket = reinterpret_cast<int32_t*>(ws + cap_alloc * sizeof(WorkItem) + 256);
-    int32_t* cursor = bucket + cap_alloc;
+    int32_t* n_work = reinterpret_cast<int32_t*>(ws + cap * sizeof(WorkItem));
+    int32_t* bucket = reinterpret_cast<int32_t*>(ws + cap * sizeof(WorkItem) + 256);
+    int32_t* cursor = bucket + cap + 1;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(build_worklist_kernel, dim3(1), dim3(1024), 0, st, cu_seqlens, (int)batch, kBM, max_qtiles,
+    hipLaunchKernelGGL(build_worklist_kernel, dim3(1), dim3(1024), 0, st, cu_seqlens, (int)batch, (int)total_tokens, kBM,
                        capacity, work, n_work, bucket, cursor);
     if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
 
@@ -550,33 +518,7 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
     p.work = work;
     p.n_work = n_work;
     p.total_tokens = (int32_t)total_tokens;
-    return launch_fwd(p, st);
-}
-
-int pec_set_option(int option, int value) {
-    switch (option) {
-        case PEC_OPT_KERNEL_VARIANT:
-            if (value < 0 || value >= N_VARIANTS) return PEC_ERR_UNSUPPORTED;
-            g_variant = value;
-            return PEC_OK;
-        case PEC_OPT_SP_MODE:
-            if (value < PEC_SP_FUSED_MERGE || value > PEC_SP_SINGLE_LAUNCH) return PEC_ERR_UNSUPPORTED;
-            g_sp_mode = value;
-            return PEC_OK;
-        default:
-            return PEC_ERR_UNSUPPORTED;
-    }
-}
-
-int pec_get_option(int option) {
-    switch (option) {
-        case PEC_OPT_KERNEL_VARIANT:
-            return g_variant;
-        case PEC_OPT_SP_MODE:
-            return g_sp_mode;
-        default:
-            return PEC_ERR_UNSUPPORTED;
-    }
+    return launch_fwd(p, (shape->flags & PEC_FLAG_SIMPLE_KERNEL) != 0, st);
 }
 
 const char* pec_status_string(int status) {

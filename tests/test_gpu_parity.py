@@ -19,15 +19,13 @@ pytestmark = pytest.mark.gpu
 O_ATOL = 2e-2
 LSE_RTOL = 1e-3
 DEV = "cuda:0"
-# default first; the last one is the slow cross-check kernel (kept out of the heavier tests)
-VARIANTS = [pec.PEC_VARIANT_INTERLEAVED, pec.PEC_VARIANT_PINGPONG, pec.PEC_VARIANT_PINGPONG_ADJ, pec.PEC_VARIANT_DMA_W8_Q32, pec.PEC_VARIANT_DMA_W4_Q64, pec.PEC_VARIANT_DMA_W4_Q32, pec.PEC_VARIANT_W8_Q32,
-            pec.PEC_VARIANT_W4_Q64, pec.PEC_VARIANT_W4_Q64_NOTR]
+# per-call kernel selection: the default pipelined kernel and the plain cross-check kernel
+KERNELS = [0, pec.PEC_FLAG_SIMPLE_KERNEL]
+SP_MODES = [0, pec.PEC_FLAG_SP_SEPARATE_MERGE, pec.PEC_FLAG_SP_SINGLE_LAUNCH]
 
 
 @pytest.fixture(autouse=True)
-def _defaults():
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, pec.PEC_VARIANT_DEFAULT)
-    pec.pec_set_option(pec.PEC_OPT_SP_MODE, pec.PEC_SP_FUSED_MERGE)
+def _sync_after():
     yield
     torch.cuda.synchronize()
 
@@ -67,35 +65,35 @@ CHUNK_CASES = [
 ]
 
 
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", KERNELS)
 @pytest.mark.parametrize("case", CHUNK_CASES)
 def test_chunk_matches_oracle(case, variant):
     sq, sk, hq, hkv, q_off, kv_off, causal = case
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     q, k, v = synth.qkv(7 + sq + sk, sq, sk, hq, hkv)
     o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=kv_off, causal=causal)
     for out_dtype in (torch.bfloat16, torch.float32):
-        out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, kv_off, causal, out_dtype=out_dtype)
+        out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, kv_off, causal, out_dtype=out_dtype, flags=variant)
         assert_close(out, lse, o_ref, l_ref, "chunk %s v%d %s" % (case, variant, out_dtype))
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:4])
+@pytest.mark.parametrize("variant", KERNELS)
 @pytest.mark.parametrize("q_off", [0, 4096])
 def test_late_jumps_of_the_row_maximum(q_off, variant):
     # keys that lift single rows' scores 16 ... 130 log2 units above the bulk, placed in tiles after the
     # first one, in masked (diagonal) and unmasked tiles: the kernels' softmax reference has to follow
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     s = 1024
     outliers = [(70, 950, 1), (300, 400, 2), (301, 1000, 4), (640, 700, 8), (900, 901, 8), (999, 1023, 2),
                 (130, 5, 4), (515, 33, 1)]   # the last two are invisible under the causal mask when q_off = 0
     q, k, v = synth.qkv_with_outlier_keys(4242, s, s, 8, 2, outliers)
     o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
-    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, 0, True, out_dtype=torch.float32)
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, 0, True, out_dtype=torch.float32, flags=variant)
     assert_close(out, lse, o_ref, l_ref, "outlier keys q_off %d v%d" % (q_off, variant))
     # and continued from a first half computed separately (fused merge across the jump)
     h = s // 2
-    o1, l1 = pec.pec_attn_chunk(*gpu(q, k[:h].contiguous(), v[:h].contiguous()), q_off, 0, True, out_dtype=torch.float32)
-    o2, l2 = pec.pec_attn_chunk_merge(*gpu(q, k[h:].contiguous(), v[h:].contiguous()), q_off, h, o1, l1, True)
+    o1, l1 = pec.pec_attn_chunk(*gpu(q, k[:h].contiguous(), v[:h].contiguous()), q_off, 0, True, out_dtype=torch.float32,
+                                flags=variant)
+    o2, l2 = pec.pec_attn_chunk_merge(*gpu(q, k[h:].contiguous(), v[h:].contiguous()), q_off, h, o1, l1, True,
+                                      flags=variant)
     assert_close(o2, l2, o_ref, l_ref, "outlier keys, two segments, q_off %d v%d" % (q_off, variant))
 
 
@@ -124,20 +122,19 @@ def test_chunk_empty_query_is_a_noop():
     assert out.shape == (0, 2, 128) and lse.shape == (2, 0)
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:4])
+@pytest.mark.parametrize("variant", KERNELS)
 @pytest.mark.parametrize("q_off,kv_off,sq,sk", [(0, 0, 600, 600), (1000, 937, 333, 700), (5, 200, 300, 90),
                                                (0, 64, 256, 256), (255, 0, 258, 515)])
 def test_mask_is_bit_exact_via_zero_query(q_off, kv_off, sq, sk, variant):
     """Q = 0 gives LSE_i = ln n_i with n_i the visible-key count; a one-hot V column gives
     exactly 1/n_i or exactly 0: any off-by-one in mask or offsets shows."""
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     hq, hkv = 4, 2
     _, k, _ = synth.qkv(11, sq, sk, hq, hkv)
     q = torch.zeros(sq, hq, 128, dtype=torch.bfloat16)
     jstar = sk // 2
     v = torch.zeros(sk, hkv, 128, dtype=torch.bfloat16)
     v[jstar] = 1.0
-    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, kv_off, True, out_dtype=torch.float32)
+    out, lse = pec.pec_attn_chunk(*gpu(q, k, v), q_off, kv_off, True, out_dtype=torch.float32, flags=variant)
     out, lse = out.cpu().numpy(), lse.cpu().numpy()
     n = np.clip(q_off + np.arange(sq) - kv_off + 1, 0, sk)
     vis = n > 0
@@ -203,9 +200,8 @@ def test_merge_matches_oracle_and_identity_is_exact(dtype):
     assert torch.equal(lse.cpu(), l_b) and torch.equal(o.cpu()[keep.T], o_b[keep.T])
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:4])
+@pytest.mark.parametrize("variant", KERNELS)
 def test_chunk_merge_folds_segments_exactly(variant):
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     sq, s, hq, hkv, q_off = 300, 900, 4, 2, 600
     q, k, v = synth.qkv(17, sq, s, hq, hkv)
     o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
@@ -218,7 +214,7 @@ def test_chunk_merge_folds_segments_exactly(variant):
     for n, c in enumerate(order):
         lo, hi = edges[c], edges[c + 1]
         pec.pec_attn_chunk_merge(qd, kd[lo:hi], vd[lo:hi], q_off, lo, o_acc, l_acc, True,
-                                 out_final=final if n == len(order) - 1 else None)
+                                 out_final=final if n == len(order) - 1 else None, flags=variant)
     assert_close(o_acc, l_acc, o_ref, l_ref, "chunk_merge acc")
     assert_close(final, l_acc, o_ref, l_ref, "chunk_merge final")
     # separate-kernel route: fp32 partials + pec_attn_merge + pec_finalize
@@ -226,46 +222,43 @@ def test_chunk_merge_folds_segments_exactly(variant):
     l2 = torch.full_like(l_acc, -math.inf)
     for c in order:
         lo, hi = edges[c], edges[c + 1]
-        o_p, l_p = pec.pec_attn_chunk(qd, kd[lo:hi], vd[lo:hi], q_off, lo, True, out_dtype=torch.float32)
+        o_p, l_p = pec.pec_attn_chunk(qd, kd[lo:hi], vd[lo:hi], q_off, lo, True, out_dtype=torch.float32,
+                                      flags=variant)
         pec.pec_attn_merge(o2, l2, o_p, l_p)
     assert_close(pec.pec_finalize(o2), l2, o_ref, l_ref, "chunk + merge + finalize")
 
 
-@pytest.mark.parametrize("mode", [pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SEPARATE_MERGE, pec.PEC_SP_SINGLE_LAUNCH])
-@pytest.mark.parametrize("variant", VARIANTS[:4])
+@pytest.mark.parametrize("mode", SP_MODES)
+@pytest.mark.parametrize("variant", KERNELS)
 def test_sp_prefill_small_config_in_full(mode, variant):
     """8 heads = 8 KV heads, seq 2048 as 4 segments of 512: every ring member, every row."""
     w = synth.WORKLOADS["c1_mha_2k"]
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
-    pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
     q, k, v = synth.qkv(w.seed, w.seq, w.seq, w.n_q_heads, w.n_kv_heads)
     o_ref, l_ref = oracle.attention(q, k, v, causal=True)
     qd, kd, vd = gpu(q, k, v)
     for r in range(w.seq // w.chunk):
         lo, hi = r * w.chunk, (r + 1) * w.chunk
-        out, lse = pec.pec_sp_prefill(qd[lo:hi], kd, vd, lo, w.chunk, True)
+        out, lse = pec.pec_sp_prefill(qd[lo:hi], kd, vd, lo, w.chunk, True, flags=mode | variant)
         assert_close(out, lse, o_ref[lo:hi], l_ref[:, lo:hi], "sp_prefill c1 member %d mode %d" % (r, mode))
 
 
-@pytest.mark.parametrize("mode", [pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SEPARATE_MERGE])
+@pytest.mark.parametrize("mode", SP_MODES[:2])
 def test_sp_prefill_ragged_and_noncausal(mode):
-    pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
     s, hq, hkv, chunk = 1000, 4, 2, 300                         # last segment has 100 tokens
     q, k, v = synth.qkv(18, s, s, hq, hkv)
     qd, kd, vd = gpu(q, k, v)
     o_ref, l_ref = oracle.attention(q, k, v, causal=True)
     for r in range(4):
         lo, hi = r * chunk, min(s, (r + 1) * chunk)
-        out, lse = pec.pec_sp_prefill(qd[lo:hi], kd, vd, lo, chunk, True, out_dtype=torch.float32)
+        out, lse = pec.pec_sp_prefill(qd[lo:hi], kd, vd, lo, chunk, True, out_dtype=torch.float32, flags=mode)
         assert_close(out, lse, o_ref[lo:hi], l_ref[:, lo:hi], "ragged member %d" % r)
     o_nc, l_nc = oracle.attention(q[300:600], k, v, causal=False)
-    out, lse = pec.pec_sp_prefill(qd[300:600], kd, vd, 300, chunk, False)
+    out, lse = pec.pec_sp_prefill(qd[300:600], kd, vd, 300, chunk, False, flags=mode)
     assert_close(out, lse, o_nc, l_nc, "non-causal ring")
 
 
-@pytest.mark.parametrize("variant", VARIANTS[:4])
+@pytest.mark.parametrize("variant", KERNELS)
 def test_varlen_matches_oracle_and_dense_calls(variant):
-    pec.pec_set_option(pec.PEC_OPT_KERNEL_VARIANT, variant)
     lengths = [5, 0, 1, 300, 257, 0, 64, 700, 256]
     cu = synth.cu_seqlens_of(lengths)
     t, hq, hkv = int(cu[-1]), 4, 2
@@ -273,19 +266,45 @@ def test_varlen_matches_oracle_and_dense_calls(variant):
     o_ref, l_ref = oracle.varlen(q, k, v, cu)
     qd, kd, vd = gpu(q, k, v)
     cud = torch.from_numpy(cu).to(DEV)
-    out, lse = pec.pec_attn_varlen(qd, kd, vd, cud, max(lengths), True)
+    out, lse = pec.pec_attn_varlen(qd, kd, vd, cud, max(lengths), True, flags=variant)
     assert_close(out, lse, o_ref, l_ref, "varlen")
     for b, n in enumerate(lengths):                 # bit-identical to one dense call per sequence
         lo, hi = int(cu[b]), int(cu[b + 1])
         if n == 0:
             continue
-        o_b, l_b = pec.pec_attn_chunk(qd[lo:hi].contiguous(), kd[lo:hi].contiguous(), vd[lo:hi].contiguous(), 0, 0)
+        o_b, l_b = pec.pec_attn_chunk(qd[lo:hi].contiguous(), kd[lo:hi].contiguous(), vd[lo:hi].contiguous(), 0, 0,
+                                      flags=variant)
         assert torch.equal(out[lo:hi], o_b) and torch.equal(lse[:, lo:hi], l_b), "sequence %d" % b
     # Q = 0: LSE = ln(position + 1) exposes any leak across sequence boundaries
-    _, lse0 = pec.pec_attn_varlen(torch.zeros_like(qd), kd, vd, cud, max(lengths), True)
+    _, lse0 = pec.pec_attn_varlen(torch.zeros_like(qd), kd, vd, cud, max(lengths), True, flags=variant)
     pos = np.concatenate([np.arange(n) for n in lengths])
     got = np.rint(np.exp(lse0.cpu().numpy().astype(np.float64))).astype(np.int64)
     assert np.array_equal(got, np.tile(pos + 1, (hq, 1)))
+
+
+def test_varlen_max_seqlen_is_only_a_hint_through_the_c_abi():
+    """A sequence longer than the max_seqlen the caller states is still processed in full: no row of
+    out / lse stays unwritten (they start as NaN) and the result matches the oracle."""
+    import ctypes
+
+    lengths = [300, 1100, 0, 17, 520]
+    cu = synth.cu_seqlens_of(lengths)
+    t, hq, hkv = int(cu[-1]), 4, 2
+    q, k, v = synth.qkv(29, t, t, hq, hkv)
+    o_ref, l_ref = oracle.varlen(q, k, v, cu)
+    qd, kd, vd = gpu(q, k, v)
+    cud = torch.from_numpy(cu).to(DEV)
+    L = pec.lib()
+    ws = torch.empty(L.pec_varlen_workspace_bytes(len(lengths), t), dtype=torch.uint8, device=DEV)
+    for max_seqlen in (1, 256, 0, max(lengths)):
+        out = torch.full((t, hq, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+        lse = torch.full((hq, t), float("nan"), dtype=torch.float32, device=DEV)
+        shp = pec.PecShape(hq, hkv, 128, pec.PEC_BF16, 0.0, 0)
+        rc = L.pec_attn_varlen(ctypes.byref(shp), qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), cud.data_ptr(),
+                               len(lengths), t, max_seqlen, 1, out.data_ptr(), lse.data_ptr(), ws.data_ptr(),
+                               ws.numel(), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0
+        assert_close(out, lse, o_ref, l_ref, "varlen with max_seqlen = %d" % max_seqlen)
 
 
 def _sampled_check(qd, kd, vd, out, lse, q_off, rows, heads=None, what=""):
@@ -311,22 +330,38 @@ def test_full_size_gqa_32k_last_member_sampled_rows():
     q_off = w.seq - w.chunk
     q, k, v = synth.qkv(w.seed, w.chunk, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
     rows = synth.sample_rows(w.seed, w.chunk, boundaries=(256, 2048), n_random=24)
-    for mode in (pec.PEC_SP_FUSED_MERGE, pec.PEC_SP_SINGLE_LAUNCH):
-        pec.pec_set_option(pec.PEC_OPT_SP_MODE, mode)
-        out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
+    for mode in (0, pec.PEC_FLAG_SP_SINGLE_LAUNCH):
+        out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True, flags=mode)
         _sampled_check(q, k, v, out, lse, q_off, rows, what="c2 mode %d" % mode)
 
 
+def _edge_rows(n_rows, edges, seed, n_random):
+    """Rows 0, +-1, +-2 around every edge, both ends of the segment, and seeded-random rows."""
+    rows = {0, 1, n_rows - 2, n_rows - 1}
+    for e in edges:
+        rows |= {e - 2, e - 1, e, e + 1, e + 2}
+    rows |= set(int(x) for x in np.random.default_rng(seed).integers(0, n_rows, size=n_random))
+    return np.array(sorted(r for r in rows if 0 <= r < n_rows), dtype=np.int64)
+
+
 def test_full_size_gqa_128k_sampled_rows():
-    """The headline shape: seq 131072 in 16 segments of 8192; members 15 (longest) and 6."""
+    """The headline shape: seq 131072 in 16 segments of 8192, launch configuration of the benchmark (one
+    pec_sp_prefill per ring member, fused merge).  Every ring member is checked on one KV head (so every KV
+    head is covered twice), on rows around a 256-row workgroup edge, a 32-row wavefront edge, both ends of
+    the segment and random rows; members 15, 6 and 0 additionally on a second KV head."""
     w = synth.WORKLOADS["c3_gqa_128k"]
     q_all, k, v = synth.qkv(w.seed, w.seq, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
-    for r, n_random in ((15, 10), (6, 10)):
+    n_members = w.seq // w.chunk
+    for r in range(n_members):
         q_off = r * w.chunk
         q = q_all[q_off:q_off + w.chunk]
         out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
-        rows = synth.sample_rows(w.seed + r, w.chunk, boundaries=(), n_random=n_random, edge=2)
-        _sampled_check(q, k, v, out, lse, q_off, rows, heads=r % w.n_kv_heads, what="c3 member %d" % r)
+        wg_edge = 256 * (1 + (5 * r) % 31)            # a workgroup (256-row) edge, different for every member
+        wave_edge = wg_edge + 32 * (1 + r % 7)        # a wavefront (32-row) edge inside the next workgroup
+        rows = _edge_rows(w.chunk, (wg_edge, wave_edge), w.seed + r, 4)
+        heads = [r % w.n_kv_heads] + ([(r + 3) % w.n_kv_heads] if r in (15, 6, 0) else [])
+        for kvh in heads:
+            _sampled_check(q, k, v, out, lse, q_off, rows, heads=kvh, what="c3 member %d kv head %d" % (r, kvh))
 
 
 def test_full_size_colocated_varlen_batch_sampled_rows():
@@ -357,8 +392,9 @@ def test_full_size_gqa_512k_last_member_sampled_rows():
     q_off = w.seq - w.chunk
     q, k, v = synth.qkv(w.seed, w.chunk, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
     out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
-    rows = synth.sample_rows(w.seed, w.chunk, boundaries=(), n_random=6, edge=1)
-    _sampled_check(q, k, v, out, lse, q_off, rows, heads=3, what="c5 last member")
+    for kvh, wg_edge, wave_edge in ((3, 256 * 17, 256 * 40 + 96), (0, 256 * 1, 256 * 63 + 32), (6, 256 * 50, 256 * 9 + 224)):
+        rows = _edge_rows(w.chunk, (wg_edge, wave_edge), w.seed + kvh, 2)
+        _sampled_check(q, k, v, out, lse, q_off, rows, heads=kvh, what="c5 last member kv head %d" % kvh)
 
 
 def test_resumable_prefill_states_match_oracle_and_survive_preemption():

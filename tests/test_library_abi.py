@@ -40,13 +40,16 @@ def test_status_strings(lib):
     assert binding.status_string(-99) == "unknown status"
 
 
-def test_options_roundtrip(lib):
-    assert lib.pec_set_option(binding.PEC_OPT_SP_MODE, binding.PEC_SP_SEPARATE_MERGE) == 0
-    assert lib.pec_get_option(binding.PEC_OPT_SP_MODE) == binding.PEC_SP_SEPARATE_MERGE
-    assert lib.pec_set_option(binding.PEC_OPT_SP_MODE, binding.PEC_SP_FUSED_MERGE) == 0
-    assert lib.pec_set_option(binding.PEC_OPT_SP_MODE, 17) == -2
-    assert lib.pec_set_option(99, 0) == -2
-    assert lib.pec_set_option(binding.PEC_OPT_KERNEL_VARIANT, -1) == -2
+def test_unknown_or_contradictory_flags_are_refused(lib):
+    S = binding.PecShape
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda flags: lib.pec_attn_chunk(ctypes.byref(S(8, 2, 128, 0, 0.0, flags)), fake, fake, fake, 0, 16, 0, 0, 1,  # noqa: E731
+                                            fake, fake, None)
+    for flags in (0, binding.PEC_FLAG_SIMPLE_KERNEL, binding.PEC_FLAG_SP_SEPARATE_MERGE,
+                  binding.PEC_FLAG_SIMPLE_KERNEL | binding.PEC_FLAG_SP_SINGLE_LAUNCH):
+        assert call(flags) == 0                      # sq = 0: accepted, nothing launched
+    assert call(8) == -2 and call(1 << 31) == -2     # unknown bits
+    assert call(binding.PEC_FLAG_SP_SEPARATE_MERGE | binding.PEC_FLAG_SP_SINGLE_LAUNCH) == -1
 
 
 def test_argument_validation_happens_on_the_host(lib):
