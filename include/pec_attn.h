@@ -42,7 +42,8 @@ typedef enum {
     PEC_ERR_UNSUPPORTED = -2,      /* head_dim != 128, unknown dtype / option, size beyond 2^30 rows */
     PEC_ERR_MISALIGNED = -3,       /* a pointer is not 16-byte aligned */
     PEC_ERR_WORKSPACE = -4,        /* workspace missing or smaller than pec_*_workspace_bytes() */
-    PEC_ERR_HIP = -5               /* the HIP runtime reported an error at launch */
+    PEC_ERR_HIP = -5,              /* the HIP runtime reported an error at launch */
+    PEC_ERR_SCRATCH_LIMIT = -6     /* pec_decode_splitkv_static: the problem needs more than the static scratch buffer */
 } pec_status;
 
 enum { PEC_BF16 = 0, PEC_F32 = 1 };
@@ -181,6 +182,27 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
                        void* stream);
 int32_t pec_decode_default_splits(const pec_shape_t* shape, int64_t sk);
 size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits);
+
+/*
+ * pec_decode_splitkv for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results (bit-identical) as pec_decode_splitkv, but the partial (O, LSE) pairs of the
+ * key ranges live in a buffer of PEC_DECODE_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (one copy per GPU, held until the process ends).  The call allocates and frees
+ * nothing, on the device or through any library.
+ *   Limit: pec_decode_workspace_bytes(shape, n_splits) = n_splits * n_q_heads * 129 * 4 bytes must
+ *   not exceed PEC_DECODE_STATIC_SCRATCH_BYTES (e.g. 128 key ranges x 64 query heads = 4.2 MB);
+ *   beyond it the call returns PEC_ERR_SCRATCH_LIMIT and launches nothing.
+ *   The first call on a device looks up the buffer's device address (hipGetSymbolAddress); make that
+ *   first call outside any stream capture.
+ *   Every call on a GPU uses that GPU's one buffer: two calls that overlap in time on the same GPU
+ *   (different streams, different threads) race on it and give undefined results.  Calls on one
+ *   stream, or otherwise ordered, are safe; nothing in the buffer needs clearing between calls
+ *   (every partial a call reads it has written itself).
+ */
+#define PEC_DECODE_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+int pec_decode_splitkv_static(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
+                              int32_t n_splits, void* out, float* lse, void* stream);
 
 /*
  * On-GPU halves of the head <-> sequence exchange of Ulysses-style sequence parallelism (section

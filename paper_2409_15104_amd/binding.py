@@ -22,7 +22,7 @@ KERNEL_NAMES = {0: "pec::fwd_il_kernel", PEC_FLAG_SIMPLE_KERNEL: "pec::fwd_simpl
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
     "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
+    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
 )
 
 
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.pec_sp_prefill_num_steps.restype = i64
         L.pec_sp_prefill_step.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, i64, vp, vp, vp, vp]
         L.pec_decode_splitkv.argtypes = [sp, vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+        L.pec_decode_splitkv_static.argtypes = [sp, vp, vp, vp, i64, i32, vp, vp, vp]
+        L.pec_decode_splitkv_static.restype = ci
         L.pec_decode_default_splits.argtypes = [sp, i64]
         L.pec_decode_default_splits.restype = i32
         L.pec_decode_workspace_bytes.argtypes = [sp, i32]
@@ -256,6 +258,16 @@ def pec_decode_splitkv(q, k, v, n_splits: int = 0, out_dtype=torch.float32, scal
     _check("pec_decode_splitkv",
            lib().pec_decode_splitkv(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), sk, int(n_splits), _ptr(out),
                                     _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out, lse
+
+
+def pec_decode_splitkv_static(q, k, v, out, lse, n_splits: int = 0, scale: float = 0.0, stream=None):
+    """pec_decode_splitkv without a workspace: partials live in the library's static device buffer.
+    `out` [1,Hq,128] (bf16 or fp32) and `lse` [Hq] are supplied by the caller; nothing is allocated."""
+    shp = _shape(q, k, out.dtype, scale)
+    _check("pec_decode_splitkv_static",
+           lib().pec_decode_splitkv_static(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), k.shape[0], int(n_splits),
+                                           _ptr(out), _ptr(lse), _stream(stream)))
     return out, lse
 
 

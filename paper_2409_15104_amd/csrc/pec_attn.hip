@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 
 #include "aux_kernels.hpp"
 #include "common.hpp"
@@ -336,19 +337,34 @@ size_t pec_decode_workspace_bytes(const pec_shape_t* shape, int32_t n_splits) {
     return (size_t)n_splits * shape->n_q_heads * (kHeadDim + 1) * sizeof(float);
 }
 
-int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
-                       int32_t n_splits, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
-    float scale;
-    if (int rc = check_shape(shape, &scale)) return rc;
-    if (sk < 0 || n_splits < 0) return PEC_ERR_INVALID_ARGUMENT;
-    if (sk > kMaxRows) return PEC_ERR_UNSUPPORTED;
-    if (!q || !out || !lse || (sk > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace))
-        return PEC_ERR_MISALIGNED;
-    if (n_splits == 0) n_splits = pec_decode_default_splits(shape, sk);
+}  // extern "C"
+
+namespace {
+
+// Scratch of pec_decode_splitkv_static: the fp32 partial (O, LSE) of every (key range, query head).
+// One copy per GPU, held until the process ends; its device address is looked up once per device.
+constexpr size_t kStaticScratchBytes = PEC_DECODE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch(void** out) {
+    static void* ptr[64] = {nullptr};
+    static std::mutex lock;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PEC_ERR_HIP;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PEC_ERR_HIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return PEC_OK;
+}
+
+// Common body of the two decode entry points; `workspace` holds pec_decode_workspace_bytes(shape, n_splits) bytes.
+int decode_impl(const pec_shape_t* shape, float scale, const void* q, const void* k, const void* v, int64_t sk,
+                int32_t n_splits, void* out, float* lse, void* workspace, void* stream) {
     const int g = shape->n_q_heads / shape->n_kv_heads;
-    if (g > 256) return PEC_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < pec_decode_workspace_bytes(shape, n_splits)) return PEC_ERR_WORKSPACE;
     float* o_part = static_cast<float*>(workspace);
     float* lse_part = o_part + (size_t)n_splits * shape->n_q_heads * kHeadDim;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -410,6 +426,41 @@ int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, c
         hipLaunchKernelGGL((combine_splits_kernel<false>), dim3(shape->n_q_heads), dim3(kCombineGroups * 128), 0, st, o_part, lse_part,
                            (int)n_splits, (int)shape->n_q_heads, out, lse);
     return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pec_decode_splitkv(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
+                       int32_t n_splits, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (sk < 0 || n_splits < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (sk > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (!q || !out || !lse || (sk > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace))
+        return PEC_ERR_MISALIGNED;
+    if (n_splits == 0) n_splits = pec_decode_default_splits(shape, sk);
+    if (shape->n_q_heads / shape->n_kv_heads > 256) return PEC_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < pec_decode_workspace_bytes(shape, n_splits)) return PEC_ERR_WORKSPACE;
+    return decode_impl(shape, scale, q, k, v, sk, n_splits, out, lse, workspace, stream);
+}
+
+int pec_decode_splitkv_static(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sk,
+                              int32_t n_splits, void* out, float* lse, void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (sk < 0 || n_splits < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (sk > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (!q || !out || !lse || (sk > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return PEC_ERR_MISALIGNED;
+    if (n_splits == 0) n_splits = pec_decode_default_splits(shape, sk);
+    if (shape->n_q_heads / shape->n_kv_heads > 256) return PEC_ERR_UNSUPPORTED;
+    if (pec_decode_workspace_bytes(shape, n_splits) > kStaticScratchBytes) return PEC_ERR_SCRATCH_LIMIT;
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return decode_impl(shape, scale, q, k, v, sk, n_splits, out, lse, ws, stream);
 }
 
 int pec_ulysses_layout(const void* src, void* dst, int64_t s, int32_t n_heads, int32_t head_dim, int32_t n_gpus,
@@ -535,6 +586,8 @@ const char* pec_status_string(int status) {
             return "workspace missing or too small";
         case PEC_ERR_HIP:
             return "HIP runtime error";
+        case PEC_ERR_SCRATCH_LIMIT:
+            return "problem needs more than the library's static scratch buffer";
         default:
             return "unknown status";
     }
