@@ -54,10 +54,15 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     constexpr int NWAVES = 8;
     constexpr int BM = NWAVES * 32;
 
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_k0[kTileBytes];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_k1[kTileBytes];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_v0[kTileBytes];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_v1[kTileBytes];
+    // One LDS block laid out by hand, the four tile stages inside the first 64 KiB: every operand read
+    // of the tile loop is then "lane offset + 16-bit immediate".  (Separate arrays are placed by the
+    // compiler in an order of its own; a stage that lands above 64 KiB needs its address in a register,
+    // and the tile loop has none to spare.)
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_all[4 * kTileBytes];
+    unsigned char* const lds_k0 = lds_all;
+    unsigned char* const lds_k1 = lds_all + kTileBytes;
+    unsigned char* const lds_v0 = lds_all + 2 * kTileBytes;
+    unsigned char* const lds_v1 = lds_all + 3 * kTileBytes;
 
     // ---- persistent workgroups: the grid holds n_slots workgroups per XCD (hardware deals block
     // ids round-robin over the 8 XCDs); each XCD owns one contiguous logical range of the
