@@ -24,10 +24,71 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 matrix peak: 256 CU x 4096 flop/clk x 2.4 GHz
 FLOP_PER_PAIR = 512.0          # per (query, key, head): 2*128 for q.k plus 2*128 for p.v
-# HBM bytes per launch of the dominant kernel (read + written), averaged over the launches of one sweep,
-# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a device copy of known size
-# (profiles/fwd_il_kernel_c3_gqa_128k_hbm_traffic.md).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"c3_gqa_128k": 4.849e8}
+
+
+def timed_steps(torch, step, steps, warmup):
+    """W untimed steps, then K timed ones between synchronisations.  Returns (wall ms per step over the
+    whole timed region, HIP-event ms of every single step): events are recorded on torch's current
+    stream, the stream every library call of this benchmark is issued on."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    return wall_ms, [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+
+
+def step_stats(ev_ms):
+    xs = sorted(ev_ms)
+    n = len(xs)
+    med = xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+    return {"median": round(med, 4), "min": round(xs[0], 4), "max": round(xs[-1], 4), "n": n}
+
+
+def mfma_probe(torch, pec, dev, iters=20000):
+    """Bare v_mfma_f32_32x32x16_bf16 loop on every compute unit: TFLOP/s on constant and on N(0,1) operands."""
+    sink = torch.empty(1024 * 512, dtype=torch.float32, device=dev)
+    res = {}
+    for name in ("constant", "normal"):
+        if name == "constant":
+            ops = torch.ones(8192, dtype=torch.bfloat16, device=dev)
+        else:
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(4711)
+            ops = torch.randn(8192, generator=gen, dtype=torch.float32, device=dev).to(torch.bfloat16)
+        flop = pec.pec_mfma_probe(ops, iters, sink)        # warm-up launch
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(3):
+            pec.pec_mfma_probe(ops, iters, sink)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / 3
+        res[name + "_operands_tflops"] = round(flop / (ms * 1e-3) / 1e12, 1)
+        res[name + "_ms"] = round(ms, 3)
+    res["what"] = ("bare v_mfma_f32_32x32x16_bf16 loop, 8 wavefronts on every compute unit, %d x 32 MFMAs per wavefront; "
+                   "the chip lowers its clock under the power limit, more so on random operand data" % iters)
+    return res
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of this workload
+    (line 'traffic_bytes_per_launch: N' in profiles/<kernel>_<workload>_hbm_traffic.md); None if there is none."""
+    path = os.path.join(ROOT, "profiles", "fwd_il_kernel_%s_hbm_traffic.md" % workload)
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def parse_args():
@@ -43,6 +104,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--decode-splits", type=int, default=0, help="key ranges per KV head for --workload decode_512k (0: library default)")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="only measure the bare MFMA rate (constant and N(0,1) operands) and print it as one JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three 1 GiB device-to-device copies (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -74,6 +137,9 @@ def main():
     pec.lib()  # fails loudly when the HIP library has not been built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.mfma_probe:
+        print(json.dumps({"mfma_probe": mfma_probe(torch, pec, dev), "nominal_peak_tflops": PEAK_BF16_TFLOPS}), flush=True)
+        return 0
     mode = {"fused": 0, "separate": pec.PEC_FLAG_SP_SEPARATE_MERGE, "single": pec.PEC_FLAG_SP_SINGLE_LAUNCH}[args.sp_mode]
     args.kernel_flag = pec.PEC_FLAG_SIMPLE_KERNEL if args.simple_kernel else 0
     args.flags = mode | args.kernel_flag
@@ -106,19 +172,8 @@ def main():
             lo = r * C
             pec.pec_sp_prefill(q[lo:lo + C], k, v, lo, C, True, out=out[lo:lo + C], lse=lse[r], workspace=ws, flags=args.flags)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = wall * 1e3 / args.steps
-    ev_ms_step = ev0.elapsed_time(ev1) / args.steps
+    ms_step, ev_ms = timed_steps(torch, step, args.steps, args.warmup)
+    ev_ms_step = sum(ev_ms) / len(ev_ms)
     tflops = flops / (ms_step * 1e-3) / 1e12
 
     # Dominant kernel = the attention kernel (every launch of the timed region in fused/single mode).
@@ -126,7 +181,7 @@ def main():
     avg_launch_ms = ev_ms_step / launches
     achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
                 "kernel": pec.KERNEL_NAMES[args.kernel_flag], "launches_per_step": launches,
                 "avg_launch_ms": round(avg_launch_ms, 4), "flop_per_launch_avg": flops / launches}
 
@@ -143,8 +198,12 @@ def main():
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "causal_useful_tflop_per_step": round(flops / 1e12, 3),
         "noncausal_convention_tflops": round(4.0 * 128 * Hq * S * S / (ms_step * 1e-3) / 1e12, 2),
+        "ms_per_step_stats": step_stats(ev_ms),
         "roofline": roofline,
     }
+    probe = mfma_probe(torch, pec, dev)     # after the timed region: the chip's bare matrix rate on this machine, now
+    result["mfma_probe"] = probe
+    result["pct_of_measured_mfma_peak"] = round(100.0 * tflops / probe["normal_operands_tflops"], 2)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, np, torch, synth, q, k, v, w)
     print(json.dumps(result), flush=True)
@@ -167,18 +226,9 @@ def bench_share(args, torch, pec, synth, dev, w, mode):
     def step():
         pec.pec_sp_prefill(q, k, v, lo, C, True, out=out, lse=lse, workspace=ws, flags=args.flags)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    avg_launch_ms = ev0.elapsed_time(ev1) / args.steps / launches
+    ms_step, ev_list = timed_steps(torch, step, args.steps, args.warmup)
+    ev_mean = sum(ev_list) / len(ev_list)
+    avg_launch_ms = ev_mean / launches
     tflops = flops / (ms_step * 1e-3) / 1e12
     achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
     result = {
@@ -191,6 +241,7 @@ def bench_share(args, torch, pec, synth, dev, w, mode):
         "tokens_per_s": round(C / (ms_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "causal_useful_tflop_per_step": round(flops / 1e12, 3),
+        "ms_per_step_stats": step_stats(ev_list),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": pec.KERNEL_NAMES[args.kernel_flag],
@@ -248,22 +299,13 @@ def bench_varlen(args, torch, np, pec, synth, dev):
     def step():
         pec.pec_attn_varlen(q, k, v, cud, max_len, True, out=out, lse=lse, workspace=ws, flags=args.kernel_flag)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_step, ev_list = timed_steps(torch, step, args.steps, args.warmup)
+    ev_mean = sum(ev_list) / len(ev_list)
+    ev_ms = ev_mean
     tflops = flops / (ms_step * 1e-3) / 1e12
     ach = flops / (ev_ms * 1e-3) / 1e12
     result = {
-        "metric": "prefill attention TFLOP/s and tokens/s at 128K GQA; % of bf16 MFMA peak",
+        "metric": "prefill attention TFLOP/s and tokens/s of the colocated packed batch; % of bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -271,6 +313,7 @@ def bench_varlen(args, torch, np, pec, synth, dev):
                                "32 q / 8 kv heads, causal per sequence" % (len(lengths), T), "total_tokens": T},
         "tokens_per_s": round(T / (ms_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "ms_per_step_stats": step_stats(ev_list),
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": pec.KERNEL_NAMES[args.kernel_flag]},
@@ -291,19 +334,10 @@ def bench_ulysses(args, torch, np, pec, synth, dev):
         pec.pec_ulysses_layout(x, G, True, out=y)
         pec.pec_ulysses_layout(y, G, False, out=z)
 
-    for _ in range(max(args.warmup, 3)):
-        step()
-    torch.cuda.synchronize()
     steps = max(args.steps, 20)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / steps
-    ev_ms = ev0.elapsed_time(ev1) / steps / 2    # per kernel launch
+    ms_step, ev_list = timed_steps(torch, step, steps, max(args.warmup, 3))
+    ev_mean = sum(ev_list) / len(ev_list)
+    ev_ms = ev_mean / 2    # per kernel launch
     gbs = algo_bytes / (ev_ms * 1e-3) / 1e9
     assert torch.equal(z, x)
     result = {
@@ -311,6 +345,7 @@ def bench_ulysses(args, torch, np, pec, synth, dev):
         "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 3), "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "ulysses_layout: [16384, 64, 128] bf16 <-> [8, 16384, 8, 128], both directions per step"},
+        "ms_per_step_stats": step_stats(ev_list),
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                      "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::ulysses_layout_kernel"},
     }
@@ -333,19 +368,10 @@ def bench_decode(args, torch, np, pec, synth, dev):
     def step():
         pec.pec_decode_splitkv(q, k, v, n_splits=n_splits, out=out, lse=lse, workspace=ws)
 
-    for _ in range(max(args.warmup, 3)):
-        step()
-    torch.cuda.synchronize()
     steps = max(args.steps, 20)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / steps
-    ev_ms = ev0.elapsed_time(ev1) / steps
+    ms_step, ev_list = timed_steps(torch, step, steps, max(args.warmup, 3))
+    ev_mean = sum(ev_list) / len(ev_list)
+    ev_ms = ev_mean
     gbs = algo_bytes / (ev_ms * 1e-3) / 1e9
     result = {
         "metric": "decode attention step over a 512K-token KV shard", "value": round(1e3 / ms_step, 1),
@@ -353,6 +379,7 @@ def bench_decode(args, torch, np, pec, synth, dev):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "decode_512k: 1 query token, 64 q / 8 kv heads, KV shard of 524288 tokens, %d key splits"
                                % n_splits},
+        "ms_per_step_stats": step_stats(ev_list),
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                      "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::decode_kernel + pec::combine_splits_kernel"},
     }

@@ -252,6 +252,19 @@ typedef struct {
 
 int pec_sp_select_strategy(const pec_sp_model_t* model, pec_sp_choice_t* choice);
 
+/*
+ * Measurement aid, not part of the method: launches a loop of independent bf16 MFMAs
+ * (v_mfma_f32_32x32x16_bf16, the instruction of the attention kernels; one workgroup of 8
+ * wavefronts per compute unit, `iters` x 32 MFMAs per wavefront) on operands the caller supplies,
+ * so that the matrix-pipe rate the chip sustains at its clocks and power limit can be measured with
+ * the caller's own timer, for constant and for random operand data.
+ *   operands: DEVICE, at least 16 KiB (8 A and 8 B fragments of 64 lanes x 16 bytes of bf16).
+ *   sink: DEVICE, at least compute units x 512 floats; receives one value per thread.
+ * Returns the number of floating-point operations the launch performs (> 0), or a negative status.
+ */
+int64_t pec_mfma_probe(const void* operands, size_t operand_bytes, int32_t iters, float* sink, size_t sink_floats,
+                       void* stream);
+
 const char* pec_status_string(int status);
 
 #ifdef __cplusplus

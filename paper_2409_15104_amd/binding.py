@@ -22,7 +22,7 @@ KERNEL_NAMES = {0: "pec::fwd_il_kernel", PEC_FLAG_SIMPLE_KERNEL: "pec::fwd_simpl
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
     "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
+    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_mfma_probe", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
 )
 
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
+        L.pec_mfma_probe.argtypes = [vp, sz, i32, vp, sz, vp]
+        L.pec_mfma_probe.restype = i64
         L.pec_status_string.argtypes = [ci]
         L.pec_status_string.restype = ctypes.c_char_p
         for name in ("pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
@@ -298,6 +300,17 @@ def pec_sp_select_strategy(d_model, n_heads, n_kv_heads, head_dim, seg_len, tp, 
     return {"attn_comm": list(c.attn_comm), "attn_compute": list(c.attn_compute), "mlp_comm": list(c.mlp_comm),
             "mlp_compute": list(c.mlp_compute), "seconds": [list(c.seconds[0]), list(c.seconds[1])],
             "best": (int(c.best_attn), int(c.best_mlp))}
+
+
+def pec_mfma_probe(operands, iters: int, sink, stream=None) -> int:
+    """Launches the bare-MFMA loop on `operands` (bf16, >= 8192 elements); returns the flop count of the launch."""
+    _require(operands, torch.bfloat16, "operands")
+    _require(sink, torch.float32, "sink")
+    n = int(lib().pec_mfma_probe(_ptr(operands), operands.numel() * 2, int(iters), _ptr(sink), sink.numel(),
+                                 _stream(stream)))
+    if n < 0:
+        raise PecError("pec_mfma_probe", n)
+    return n
 
 
 def pec_varlen_workspace_bytes(batch: int, total_tokens: int) -> int:

@@ -15,6 +15,7 @@
 #include "decode_kernel.hpp"
 #include "fwd_kernel.hpp"
 #include "fwd_kernel_il.hpp"
+#include "mfma_probe.hpp"
 
 namespace {
 
@@ -570,6 +571,20 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
     p.n_work = n_work;
     p.total_tokens = (int32_t)total_tokens;
     return launch_fwd(p, (shape->flags & PEC_FLAG_SIMPLE_KERNEL) != 0, st);
+}
+
+int64_t pec_mfma_probe(const void* operands, size_t operand_bytes, int32_t iters, float* sink, size_t sink_floats,
+                       void* stream) {
+    const size_t need = (size_t)kProbeFrags * 2 * 64 * 16;
+    if (!operands || !sink || iters <= 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return PEC_ERR_MISALIGNED;
+    const int grid = compute_units();
+    if (operand_bytes < need || sink_floats < (size_t)grid * kProbeWaves * 64) return PEC_ERR_WORKSPACE;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(grid), dim3(kProbeWaves * 64), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(operands), (int)iters, sink);
+    if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+    // flop of the launch: every MFMA is 32 x 32 x 16 multiply-adds
+    return (int64_t)grid * kProbeWaves * iters * kProbeMfmaPerIter * (2LL * 32 * 32 * 16);
 }
 
 const char* pec_status_string(int status) {
