@@ -18,6 +18,9 @@ marshals numpy arrays into it and writes out the segment/ring bookkeeping:
 * :func:`varlen`     -- a packed batch of independent prompts (the batched short
   prefills of section "Coordinated Prefill-Decode Colocation and
   Disaggregation"): each sequence attends only to itself, positions restart at 0.
+* :func:`colocated`  -- the mixed batch of the same section: every sequence brings its own number of
+  queries (the last positions of the sequence) and of keys; a decode step is one query against its
+  whole cache, a prompt has as many queries as keys.
 
 Parity pins: tests/test_oracle_pins.py.
 """
@@ -230,4 +233,27 @@ def varlen(q, k, v, cu_seqlens, *, causal: bool = True, scale: float | None = No
         o_b, l_b = attention(qa[lo:hi], ka[lo:hi], va[lo:hi], q_off=0, kv_off=0, causal=causal, scale=scale)
         out[lo:hi] = o_b
         lse[:, lo:hi] = l_b
+    return out, lse
+
+
+def colocated(q, k, v, cu_seqlens_q, cu_seqlens_k, *, causal: bool = True, scale: float | None = None):
+    """Mixed batch of prefills and decode steps: sequence b owns query rows cu_q[b]..cu_q[b+1]-1 and key
+    rows cu_k[b]..cu_k[b+1]-1; its len_q queries are the last len_q positions of its len_k tokens, so
+    query i sits at position len_k - len_q + i and sees keys 0 .. len_k - len_q + i (Eq. 3)."""
+    qa, _ = _as_input(q)
+    ka, _ = _as_input(k)
+    va, _ = _as_input(v)
+    cq = [int(x) for x in np.asarray(cu_seqlens_q).reshape(-1)]
+    ck = [int(x) for x in np.asarray(cu_seqlens_k).reshape(-1)]
+    total, hq, d = qa.shape
+    out = np.zeros((total, hq, d), dtype=np.float64)
+    lse = np.full((hq, total), -np.inf, dtype=np.float64)
+    for b in range(len(cq) - 1):
+        q0, q1, k0, k1 = cq[b], cq[b + 1], ck[b], ck[b + 1]
+        if q1 <= q0:
+            continue
+        o_b, l_b = attention(qa[q0:q1], ka[k0:k1], va[k0:k1], q_off=(k1 - k0) - (q1 - q0), kv_off=0, causal=causal,
+                             scale=scale)
+        out[q0:q1] = o_b
+        lse[:, q0:q1] = l_b
     return out, lse

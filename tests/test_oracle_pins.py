@@ -287,6 +287,53 @@ def test_varlen_is_per_sequence_dense_and_leak_free():
     assert np.array_equal(np.rint(np.exp(lse0)).astype(int), np.tile(pos + 1, (hq, 1)))
 
 
+def test_colocated_batch_decode_rows_are_rows_of_the_full_prefill():
+    """The mixed batch against three things it must reduce to: literal Eq. 3 per sequence with the
+    queries placed at the END of the keys; the packed self-attention batch when every sequence has as
+    many queries as keys; and, for a decode step or a chunk of new tokens, the corresponding LAST rows
+    of the causal self-attention over the whole sequence (what decoding token t means)."""
+    hq, hkv, d = 4, 2, 8
+    len_q = [5, 1, 0, 3, 1, 4, 2]
+    len_k = [5, 9, 4, 7, 1, 4, 1]          # prompt, decode, no query, chunk behind a prefix, first token, prompt, more queries than keys
+    cq, ck = synth.cu_seqlens_of(len_q), synth.cu_seqlens_of(len_k)
+    tq, tk = int(cq[-1]), int(ck[-1])
+    q, k, v = _rand((tq, hq, d), 63), _rand((tk, hkv, d), 64), _rand((tk, hkv, d), 65)
+    o, lse = oracle.colocated(q, k, v, cq, ck)
+    for b, (nq, nk) in enumerate(zip(len_q, len_k)):
+        q0, k0 = int(cq[b]), int(ck[b])
+        if nq == 0:
+            continue
+        o_b, l_b = brute_force(q[q0:q0 + nq], k[k0:k0 + nk], v[k0:k0 + nk], nk - nq, 0, True, 1 / math.sqrt(d))
+        np.testing.assert_allclose(o[q0:q0 + nq], o_b, rtol=0, atol=1e-12)
+        fin = np.isfinite(l_b)
+        assert np.array_equal(np.isfinite(lse[:, q0:q0 + nq]), fin)
+        np.testing.assert_allclose(lse[:, q0:q0 + nq][fin], l_b[fin], rtol=0, atol=1e-12)
+    # the sequence with more queries than keys: its first query lies before position 0 and sees nothing
+    q0 = int(cq[6])
+    assert np.all(lse[:, q0] == -np.inf) and np.all(o[q0] == 0) and np.all(np.isfinite(lse[:, q0 + 1]))
+    # Q = 0: LSE = ln(number of visible keys) = ln(len_k - len_q + i + 1), clipped at 0 keys
+    _, lse0 = oracle.colocated(np.zeros_like(q), k, v, cq, ck)
+    want = np.concatenate([np.clip(nk - nq + np.arange(nq) + 1, 0, nk) for nq, nk in zip(len_q, len_k)])
+    got = np.where(np.isfinite(lse0), np.rint(np.exp(lse0)), 0).astype(int)
+    assert np.array_equal(got, np.tile(want, (hq, 1)))
+    # equal offsets: the packed self-attention batch
+    lens = [5, 0, 1, 9, 3]
+    cu = synth.cu_seqlens_of(lens)
+    t = int(cu[-1])
+    q2, k2, v2 = _rand((t, hq, d), 66), _rand((t, hkv, d), 67), _rand((t, hkv, d), 68)
+    o_c, l_c = oracle.colocated(q2, k2, v2, cu, cu)
+    o_v, l_v = oracle.varlen(q2, k2, v2, cu)
+    assert np.array_equal(o_c, o_v) and np.array_equal(l_c, l_v)
+    # decode step / chunk = the last rows of the full causal prefill of that sequence
+    n = 11
+    qf, kf, vf = _rand((n, hq, d), 69), _rand((n, hkv, d), 70), _rand((n, hkv, d), 71)
+    o_full, l_full = oracle.attention(qf, kf, vf, causal=True)
+    for tail in (1, 4):
+        o_t, l_t = oracle.colocated(qf[n - tail:], kf, vf, np.array([0, tail]), np.array([0, n]))
+        np.testing.assert_allclose(o_t, o_full[n - tail:], rtol=0, atol=1e-13)
+        np.testing.assert_allclose(l_t, l_full[:, n - tail:], rtol=0, atol=1e-13)
+
+
 def test_input_recipe_statistics():
     lens = synth.lognormal_lengths(synth.VARLEN_SEED, 20000)
     assert 650 <= np.median(lens) <= 750
