@@ -6,7 +6,7 @@ segment r = 0..P-1 runs pec_sp_prefill over the KV segments it can see, in ring
 order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c4_varlen|decode_512k|ulysses_layout]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c5_gqa_512k|c4_varlen|c4_colocated|decode_512k|ulysses_layout]
                   [--sp-mode fused|separate|single] [--simple-kernel] [--share] [--no-cpu-baseline]
 """
 from __future__ import annotations
@@ -146,6 +146,8 @@ def main():
 
     if args.workload == "c4_varlen":
         return bench_varlen(args, torch, np, pec, synth, dev)
+    if args.workload == "c4_colocated":
+        return bench_colocated(args, torch, np, pec, synth, dev)
     if args.workload.startswith("decode"):
         return bench_decode(args, torch, np, pec, synth, dev)
     if args.workload.startswith("ulysses"):
@@ -317,6 +319,63 @@ def bench_varlen(args, torch, np, pec, synth, dev):
         "roofline": {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": pec.KERNEL_NAMES[args.kernel_flag]},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_colocated(args, torch, np, pec, synth, dev):
+    """The colocation case of the paper: 256 log-normal short prompts batched with the decode step of a long
+    request whose KV cache holds 524,288 tokens (32 q / 8 kv heads), one pec_attn_colocated call."""
+    Hq, Hkv, cache = 32, 8, 524288
+    short = synth.lognormal_lengths(synth.VARLEN_SEED, synth.VARLEN_N_SHORT)
+    len_q = np.concatenate([short, [1]])
+    len_k = np.concatenate([short, [cache]])
+    cq, ck = synth.cu_seqlens_of(len_q), synth.cu_seqlens_of(len_k)
+    Tq, Tk = int(cq[-1]), int(ck[-1])
+    q, _, _ = synth.qkv(synth.VARLEN_SEED, Tq, 1, Hq, Hkv, device=dev)
+    _, k, v = synth.qkv(synth.VARLEN_SEED + 1, 1, Tk, Hq, Hkv, device=dev)
+    cqd, ckd = torch.from_numpy(cq).to(dev), torch.from_numpy(ck).to(dev)
+    out = torch.empty_like(q)
+    lse = torch.empty((Hq, Tq), dtype=torch.float32, device=dev)
+    shp = pec.PecShape(Hq, Hkv, 128, pec.PEC_BF16, 0.0, 0)
+    ws = torch.empty(int(pec.lib().pec_colocated_workspace_bytes(ctypes.byref(shp), len(len_q), Tq, Tk)), dtype=torch.uint8,
+                     device=dev)
+    pairs = int(sum(int(n) * (int(n) + 1) // 2 for n in short)) + cache
+    flops = FLOP_PER_PAIR * Hq * pairs
+    decode_bytes = 2.0 * cache * Hkv * 128 * 2                # K and V of the long request, read once
+
+    def step():
+        pec.pec_attn_colocated(q, k, v, cqd, ckd, True, out=out, lse=lse, workspace=ws)
+
+    ms_step, ev_list = timed_steps(torch, step, args.steps, args.warmup)
+    ev_ms = sum(ev_list) / len(ev_list)
+    tflops = flops / (ms_step * 1e-3) / 1e12
+    # for comparison: the two parts as separate calls
+    qs, ks, vs = q[:Tq - 1], k[:Tk - cache], v[:Tk - cache]
+    cus = torch.from_numpy(synth.cu_seqlens_of(short)).to(dev)
+    ws2 = torch.empty(pec.pec_varlen_workspace_bytes(len(short), Tq - 1), dtype=torch.uint8, device=dev)
+    _, ev_p = timed_steps(torch, lambda: pec.pec_attn_varlen(qs, ks, vs, cus, int(short.max()), True, out=out[:Tq - 1],
+                                                            lse=lse[:, :Tq - 1].contiguous(), workspace=ws2), args.steps, 1)
+    o1 = torch.empty((1, Hq, 128), dtype=torch.float32, device=dev)
+    l1 = torch.empty((Hq,), dtype=torch.float32, device=dev)
+    _, ev_d = timed_steps(torch, lambda: pec.pec_decode_splitkv(q[Tq - 1:], k[Tk - cache:], v[Tk - cache:], out=o1, lse=l1),
+                          args.steps, 1)
+    result = {
+        "metric": "colocated batch (short prefills + one long-request decode step) per launch; attention TFLOP/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_colocated: 256 log-normal short prompts (%d tokens) + the decode step of a request with "
+                               "%d cached tokens, 32 q / 8 kv heads, one pec_attn_colocated call" % (Tq - 1, cache)},
+        "tokens_per_s": round(Tq / (ms_step * 1e-3), 1),
+        "ms_per_step_stats": step_stats(ev_list),
+        "separate_calls_ms": {"pec_attn_varlen (prefills)": round(sum(ev_p) / len(ev_p), 3),
+                              "pec_decode_splitkv (decode)": round(sum(ev_d) / len(ev_d), 3)},
+        "decode_bytes_per_step": decode_bytes,
+        "roofline": {"bound": "mfma", "achieved": round(flops / (ev_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(flops / (ev_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": "pec::fwd_il_kernel"},
     }
     print(json.dumps(result), flush=True)
     return 0

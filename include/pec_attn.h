@@ -166,6 +166,30 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
 size_t pec_varlen_workspace_bytes(int32_t batch, int64_t total_tokens);
 
 /*
+ * Colocated batch in ONE attention launch (section "Coordinated Prefill-Decode Colocation and
+ * Disaggregation": the GPUs that hold a long request's KV cache run its decode step batched together
+ * with the prefills of short requests).  Sequence b has len_q = cu_seqlens_q[b+1] - cu_seqlens_q[b]
+ * query tokens (rows of q / out) and len_k = cu_seqlens_k[b+1] - cu_seqlens_k[b] keys (rows of k / v);
+ * its queries are the LAST len_q positions of the sequence, query i at position len_k - len_q + i, so
+ * with causal != 0 key j is visible to query i iff j <= len_k - len_q + i (Eq. 3).  A prompt has
+ * len_q == len_k; the decode step of a request has len_q == 1 and len_k = its cache length including
+ * the new token; anything in between is a chunk of new tokens behind a cached prefix.
+ *   q, out [total_q, Hq, 128]; k, v [total_k, Hkv, 128]; lse [Hq, total_q].
+ *   cu_seqlens_q, cu_seqlens_k: DEVICE int32 [batch + 1], non-decreasing from 0 (values are clamped on
+ *   the device; malformed ones can misplace or drop results but never index out of bounds).
+ * One-token sequences with more than 4096 keys are cut into key ranges of 4096 keys that run as work
+ * items of the same launch (the query heads of a KV group share one pass over the keys); a second,
+ * small launch merges their partial (O, LSE) pairs by log-sum-exp.  Rows without a visible key get
+ * out = 0, lse = -inf.  workspace: pec_colocated_workspace_bytes() bytes.
+ * PEC_FLAG_SIMPLE_KERNEL is not supported here (PEC_ERR_UNSUPPORTED).
+ */
+int pec_attn_colocated(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                       const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int32_t batch,
+                       int64_t total_q, int64_t total_k, int causal, void* out, float* lse,
+                       void* workspace, size_t workspace_bytes, void* stream);
+size_t pec_colocated_workspace_bytes(const pec_shape_t* shape, int32_t batch, int64_t total_q, int64_t total_k);
+
+/*
  * Decode attention of a long request kept on its prefill GPUs while short prefills share them
  * (section "Coordinated Prefill-Decode Colocation and Disaggregation"): ONE new token, q [1, Hq, 128],
  * against this GPU's shard of the KV cache, k/v [sk, Hkv, 128]; every key is visible.  The shard is

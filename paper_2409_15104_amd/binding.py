@@ -22,7 +22,7 @@ KERNEL_NAMES = {0: "pec::fwd_il_kernel", PEC_FLAG_SIMPLE_KERNEL: "pec::fwd_simpl
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
     "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_mfma_probe", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
+    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_mfma_probe", "pec_attn_colocated", "pec_colocated_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
 )
 
 
@@ -85,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.pec_attn_varlen.argtypes = [sp, vp, vp, vp, vp, i32, i64, i32, ci, vp, vp, vp, sz, vp]
         L.pec_varlen_workspace_bytes.argtypes = [i32, i64]
         L.pec_varlen_workspace_bytes.restype = sz
+        L.pec_attn_colocated.argtypes = [sp, vp, vp, vp, vp, vp, i32, i64, i64, ci, vp, vp, vp, sz, vp]
+        L.pec_attn_colocated.restype = ci
+        L.pec_colocated_workspace_bytes.argtypes = [sp, i32, i64, i64]
+        L.pec_colocated_workspace_bytes.restype = sz
         L.pec_mfma_probe.argtypes = [vp, sz, i32, vp, sz, vp]
         L.pec_mfma_probe.restype = i64
         L.pec_status_string.argtypes = [ci]
@@ -300,6 +304,31 @@ def pec_sp_select_strategy(d_model, n_heads, n_kv_heads, head_dim, seg_len, tp, 
     return {"attn_comm": list(c.attn_comm), "attn_compute": list(c.attn_compute), "mlp_comm": list(c.mlp_comm),
             "mlp_compute": list(c.mlp_compute), "seconds": [list(c.seconds[0]), list(c.seconds[1])],
             "best": (int(c.best_attn), int(c.best_mlp))}
+
+
+def pec_attn_colocated(q, k, v, cu_seqlens_q, cu_seqlens_k, causal: bool = True, out_dtype=torch.bfloat16,
+                       scale: float = 0.0, flags: int = 0, out=None, lse=None, workspace=None, stream=None):
+    """Colocated batch: q [Tq,Hq,128], k/v [Tk,Hkv,128], separate int32 offsets [B+1] for queries and keys."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    _require(cu_seqlens_q, torch.int32, "cu_seqlens_q")
+    _require(cu_seqlens_k, torch.int32, "cu_seqlens_k")
+    total_q, hq, d = q.shape
+    total_k = k.shape[0]
+    batch = cu_seqlens_q.numel() - 1
+    if out is None:
+        out = torch.empty((total_q, hq, d), dtype=out_dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((hq, total_q), dtype=torch.float32, device=q.device)
+    shp = _shape(q, k, out_dtype, scale, flags)
+    if workspace is None:
+        workspace = torch.empty(max(16, int(lib().pec_colocated_workspace_bytes(ctypes.byref(shp), batch, total_q, total_k))),
+                                dtype=torch.uint8, device=q.device)
+    _check("pec_attn_colocated",
+           lib().pec_attn_colocated(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens_q), _ptr(cu_seqlens_k),
+                                    batch, total_q, total_k, int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace),
+                                    workspace.numel(), _stream(stream)))
+    return out, lse
 
 
 def pec_mfma_probe(operands, iters: int, sink, stream=None) -> int:

@@ -38,8 +38,8 @@ constexpr int kTileBytes = kBN * kRowBytes;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-struct WorkItem {   // one (sequence, query tile) of a packed batch
-    int32_t seq;
+struct WorkItem {   // one (sequence, query tile) of a packed batch; in a colocated batch a negative
+    int32_t seq;    // qtile stands for key range number -1 - qtile of a one-token (decode) sequence
     int32_t qtile;
 };
 
@@ -72,6 +72,16 @@ struct FwdParams {
     // element strides of q / out / acc between rows and between heads (0 = the packed
     // [tokens, n_q_heads, 128] layout; fwd_il_kernel only)
     int64_t q_row_stride, q_head_stride;
+    // colocated batch (cu_seqlens_k != null; fwd_il_kernel only): sequence b has queries
+    // cu_seqlens[b] .. and keys cu_seqlens_k[b] ..; its query i sits at position len_k - len_q + i.
+    // One-token sequences with long caches are cut into key ranges of coloc_range_len keys whose
+    // partial results go to part_out / part_lse at slot seq_slot0[seq] + range.
+    const int32_t* cu_seqlens_k;
+    const int32_t* seq_slot0;
+    float* part_out;            // [slots][n_q_heads][128] fp32
+    float* part_lse;            // [slots][n_q_heads]
+    int32_t total_k;            // rows of the packed k / v arrays
+    int32_t coloc_range_len;    // keys per range, a multiple of 64
 };
 
 __device__ __forceinline__ uint32_t k_lds_off(int key, int chunk16) {

@@ -91,31 +91,66 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     const int item = rem / p.group;
     const int head = kvh * p.group + rem % p.group;
 
+    // Per-item geometry and addressing: rows sq x keys sk with diagonal offset delta; element offsets of
+    // row 0 in q (q_off0), in out / acc (o_off0) and in lse (lse_off0), the row stride of q / out / acc.
     int sq, sk, delta, qt;
-    int64_t q_tok0, kv_tok0;
+    int64_t kv_tok0, q_off0, o_off0, lse_off0;
+    int64_t q_stride = p.q_row_stride ? p.q_row_stride : (int64_t)p.n_q_heads * kHeadDim;
+    void* out_ptr = p.out;
+    float* lse_ptr = p.lse;
+    int out_f32 = p.out_f32;
     if (p.cu_seqlens) {
         if (item >= *p.n_work) continue;
         const WorkItem w = p.work[item];
         const int b0 = min(max(p.cu_seqlens[w.seq], 0), p.total_tokens);
         const int b1 = min(max(p.cu_seqlens[w.seq + 1], b0), p.total_tokens);
-        sq = sk = b1 - b0;
-        delta = 0;
-        qt = w.qtile;
-        q_tok0 = kv_tok0 = b0;
+        int k0 = b0, k1 = b1;
+        if (p.cu_seqlens_k) {
+            k0 = min(max(p.cu_seqlens_k[w.seq], 0), p.total_k);
+            k1 = min(max(p.cu_seqlens_k[w.seq + 1], k0), p.total_k);
+        }
+        if (w.qtile >= 0) {   // a query tile of a prompt: its rows are the last b1 - b0 positions of k1 - k0
+            sq = b1 - b0;
+            sk = k1 - k0;
+            delta = sk - sq;
+            qt = w.qtile;
+            kv_tok0 = k0;
+            q_off0 = b0 * q_stride + (int64_t)head * kHeadDim;
+            o_off0 = q_off0;
+            lse_off0 = (int64_t)head * p.lse_stride + b0;
+        } else {              // a key range of a one-token sequence: the heads of a KV group are the rows
+            if (rem % p.group != 0) continue;   // one unit per KV head
+            const int r = -1 - w.qtile;
+            const int64_t slot_no = (int64_t)p.seq_slot0[w.seq] + r;
+            sq = p.group;
+            kv_tok0 = (int64_t)k0 + (int64_t)r * p.coloc_range_len;
+            sk = (int)max((int64_t)0, min((int64_t)p.coloc_range_len, (int64_t)k1 - kv_tok0));
+            delta = sk;       // every key of the range is visible
+            qt = 0;
+            q_off0 = b0 * q_stride + (int64_t)kvh * p.group * kHeadDim;
+            q_stride = kHeadDim;
+            o_off0 = (slot_no * p.n_q_heads + (int64_t)kvh * p.group) * kHeadDim;
+            lse_off0 = slot_no * p.n_q_heads + (int64_t)kvh * p.group;
+            out_ptr = p.part_out;
+            lse_ptr = p.part_lse;
+            out_f32 = 1;
+        }
     } else {
         sq = p.sq;
         sk = p.sk;
         delta = p.delta;
         qt = p.causal ? (p.n_items - 1 - item) : item;  // longest rows first
-        q_tok0 = kv_tok0 = 0;
-    }
-    int64_t split_out = 0, split_lse = 0;
-    if (p.kv_split_len > 0) {   // the work item is a key range; all of it is visible (decode)
-        qt = 0;
-        kv_tok0 = (int64_t)item * p.kv_split_len;
-        sk = (int)max((int64_t)0, min((int64_t)p.kv_split_len, (int64_t)p.sk - kv_tok0));
-        split_out = item * p.split_out_stride;
-        split_lse = item * p.split_lse_stride;
+        kv_tok0 = 0;
+        q_off0 = (int64_t)head * (p.q_head_stride ? p.q_head_stride : kHeadDim);
+        o_off0 = q_off0;
+        lse_off0 = (int64_t)head * p.lse_stride;
+        if (p.kv_split_len > 0) {   // the work item is a key range; all of it is visible (decode)
+            qt = 0;
+            kv_tok0 = (int64_t)item * p.kv_split_len;
+            sk = (int)max((int64_t)0, min((int64_t)p.kv_split_len, (int64_t)p.sk - kv_tok0));
+            o_off0 += item * p.split_out_stride;
+            lse_off0 += item * p.split_lse_stride;
+        }
     }
     const int causal = p.causal;
     const int row0 = qt * BM;
@@ -138,8 +173,6 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     n_act = max(n_act, n_full);
     if (rw0 >= sq) n_full = n_act = 0;   // a wavefront without a valid row only helps loading tiles
 
-    const int64_t q_stride = p.q_row_stride ? p.q_row_stride : (int64_t)p.n_q_heads * kHeadDim;
-    const int64_t q_head_off = (int64_t)head * (p.q_head_stride ? p.q_head_stride : kHeadDim);
     const uint32_t kv_stride_b = (uint32_t)p.n_kv_heads * kHeadDim * 2;   // bytes per token
     const unsigned char* kbase =
         reinterpret_cast<const unsigned char*>(p.k) + (kv_tok0 * p.n_kv_heads + kvh) * (int64_t)(kHeadDim * 2);
@@ -150,7 +183,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     bf16x8 qf[8];
     {
         const int row = rw0 + l32;
-        const __bf16* qrow = p.q + (q_tok0 + row) * q_stride + q_head_off + 8 * hl;
+        const __bf16* qrow = p.q + q_off0 + row * q_stride + 8 * hl;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             u32x4 raw = {0u, 0u, 0u, 0u};
@@ -169,11 +202,11 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     if (p.acc_in) {
         const int row = rw0 + l32;
         if (row < sq) {
-            const float lin = p.lse_in[(int64_t)head * p.lse_stride + q_tok0 + row];
+            const float lin = p.lse_in[lse_off0 + row];
             if (lin != -INFINITY) {
                 m_run = lin * kLog2e;
                 l_run = hl == 0 ? 1.f : 0.f;
-                const float* arow = p.acc_in + (q_tok0 + row) * q_stride + q_head_off + 4 * hl;
+                const float* arow = p.acc_in + o_off0 + row * q_stride + 4 * hl;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -549,8 +582,8 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         if (row < sq) {
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-            if (hl == 0) p.lse[split_lse + (int64_t)head * p.lse_stride + q_tok0 + row] = lse;
-            const int64_t obase = split_out + (q_tok0 + row) * q_stride + q_head_off + 4 * hl;
+            if (hl == 0) lse_ptr[lse_off0 + row] = lse;
+            const int64_t obase = o_off0 + row * q_stride + 4 * hl;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -560,11 +593,11 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                     for (int i = 0; i < 4; ++i) x[i] = o[dt][4 * b + i] * inv;
                     const int64_t idx = obase + 32 * dt + 8 * b;
                     if (p.acc_out) *reinterpret_cast<f32x4*>(p.acc_out + idx) = x;
-                    if (p.out) {
-                        if (p.out_f32)
-                            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = x;
+                    if (out_ptr) {
+                        if (out_f32)
+                            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out_ptr) + idx) = x;
                         else
-                            *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + idx) =
+                            *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(out_ptr) + idx) =
                                 __builtin_convertvector(x, bf16x4);
                     }
                 }

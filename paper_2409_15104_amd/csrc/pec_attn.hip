@@ -573,6 +573,105 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
     return launch_fwd(p, (shape->flags & PEC_FLAG_SIMPLE_KERNEL) != 0, st);
 }
 
+namespace {
+constexpr int kColocRange = 4096;   // keys per range of a split one-token sequence (64 tiles)
+struct ColocLayout {
+    size_t cap_items, n_buckets, slot_cap;
+    size_t off_counters, off_bucket, off_cursor, off_slot0, off_split, off_part_lse, off_part_out, bytes;
+};
+ColocLayout coloc_layout(int n_q_heads, int32_t batch, int64_t total_q, int64_t total_k) {
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    ColocLayout L;
+    L.slot_cap = (size_t)(total_k / kColocRange) + (size_t)batch;
+    L.cap_items = (size_t)(total_q / kBM) + (size_t)batch + L.slot_cap + 1;
+    L.n_buckets = (size_t)(total_k / 256) + 2;
+    size_t o = up(L.cap_items * sizeof(WorkItem));
+    L.off_counters = o;  o += 256;
+    L.off_bucket = o;    o = up(o + (L.n_buckets + 1) * sizeof(int32_t));
+    L.off_cursor = o;    o = up(o + L.n_buckets * sizeof(int32_t));
+    L.off_slot0 = o;     o = up(o + (size_t)batch * sizeof(int32_t));
+    L.off_split = o;     o = up(o + (size_t)batch * sizeof(SplitSeq));
+    L.off_part_lse = o;  o = up(o + L.slot_cap * n_q_heads * sizeof(float));
+    L.off_part_out = o;  o = up(o + L.slot_cap * n_q_heads * kHeadDim * sizeof(float));
+    L.bytes = o;
+    return L;
+}
+}  // namespace
+
+size_t pec_colocated_workspace_bytes(const pec_shape_t* shape, int32_t batch, int64_t total_q, int64_t total_k) {
+    if (!shape || shape->n_q_heads <= 0 || batch < 0 || total_q < 0 || total_k < 0) return 0;
+    return coloc_layout(shape->n_q_heads, batch, total_q, total_k).bytes;
+}
+
+int pec_attn_colocated(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                       const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int32_t batch, int64_t total_q,
+                       int64_t total_k, int causal, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    float scale;
+    if (int rc = check_shape(shape, &scale)) return rc;
+    if (shape->flags & PEC_FLAG_SIMPLE_KERNEL) return PEC_ERR_UNSUPPORTED;   // the plain kernel knows no key ranges
+    if (batch < 0 || total_q < 0 || total_k < 0) return PEC_ERR_INVALID_ARGUMENT;
+    if (total_q > kMaxRows || total_k > kMaxRows) return PEC_ERR_UNSUPPORTED;
+    if (batch == 0 || total_q == 0) return PEC_OK;
+    if (!q || !out || !lse || !cu_seqlens_q || !cu_seqlens_k || (total_k > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace) ||
+        (reinterpret_cast<uintptr_t>(cu_seqlens_q) & 3u) || (reinterpret_cast<uintptr_t>(cu_seqlens_k) & 3u))
+        return PEC_ERR_MISALIGNED;
+    const ColocLayout L = coloc_layout(shape->n_q_heads, batch, total_q, total_k);
+    if (!workspace || workspace_bytes < L.bytes) return PEC_ERR_WORKSPACE;
+    if (L.cap_items > 0x7fffffff || L.n_buckets > 0x7fffffff) return PEC_ERR_UNSUPPORTED;
+
+    char* ws = static_cast<char*>(workspace);
+    WorkItem* work = reinterpret_cast<WorkItem*>(ws);
+    int32_t* counters = reinterpret_cast<int32_t*>(ws + L.off_counters);
+    int32_t* seq_slot0 = reinterpret_cast<int32_t*>(ws + L.off_slot0);
+    SplitSeq* split_seqs = reinterpret_cast<SplitSeq*>(ws + L.off_split);
+    float* part_lse = reinterpret_cast<float*>(ws + L.off_part_lse);
+    float* part_out = reinterpret_cast<float*>(ws + L.off_part_out);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(build_colocated_worklist_kernel, dim3(1), dim3(1024), 0, st, cu_seqlens_q, cu_seqlens_k, (int)batch,
+                       (int)total_q, (int)total_k, kBM, kColocRange, (int)L.cap_items, (int)L.slot_cap, (int)L.n_buckets,
+                       work, counters, reinterpret_cast<int32_t*>(ws + L.off_bucket),
+                       reinterpret_cast<int32_t*>(ws + L.off_cursor), seq_slot0, split_seqs);
+    if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+
+    FwdParams p{};
+    p.q = static_cast<const __bf16*>(q);
+    p.k = static_cast<const __bf16*>(k);
+    p.v = static_cast<const __bf16*>(v);
+    p.out = out;
+    p.lse = lse;
+    p.lse_stride = total_q;
+    p.causal = causal ? 1 : 0;
+    p.n_q_heads = shape->n_q_heads;
+    p.n_kv_heads = shape->n_kv_heads;
+    p.group = shape->n_q_heads / shape->n_kv_heads;
+    if (p.group > 256) return PEC_ERR_UNSUPPORTED;   // the heads of a KV group are the rows of one query tile
+    p.n_items = (int32_t)L.cap_items;
+    p.out_f32 = shape->out_dtype == PEC_F32;
+    p.scale_log2 = scale * kLog2e;
+    p.cu_seqlens = cu_seqlens_q;
+    p.work = work;
+    p.n_work = counters;
+    p.total_tokens = (int32_t)total_q;
+    p.cu_seqlens_k = cu_seqlens_k;
+    p.seq_slot0 = seq_slot0;
+    p.part_out = part_out;
+    p.part_lse = part_lse;
+    p.total_k = (int32_t)total_k;
+    p.coloc_range_len = kColocRange;
+    if (int rc = launch_fwd(p, false, st)) return rc;
+
+    const dim3 grid((unsigned)shape->n_q_heads, (unsigned)std::min<int32_t>(batch, 1024));
+    if (shape->out_dtype == PEC_F32)
+        hipLaunchKernelGGL((combine_colocated_kernel<true>), grid, dim3(kCombineGroups * 128), 0, st, part_out, part_lse,
+                           split_seqs, counters + 2, cu_seqlens_q, (int)total_q, (int)shape->n_q_heads, out, lse);
+    else
+        hipLaunchKernelGGL((combine_colocated_kernel<false>), grid, dim3(kCombineGroups * 128), 0, st, part_out, part_lse,
+                           split_seqs, counters + 2, cu_seqlens_q, (int)total_q, (int)shape->n_q_heads, out, lse);
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
+}
+
 int64_t pec_mfma_probe(const void* operands, size_t operand_bytes, int32_t iters, float* sink, size_t sink_floats,
                        void* stream) {
     const size_t need = (size_t)kProbeFrags * 2 * 64 * 16;

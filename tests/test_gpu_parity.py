@@ -307,6 +307,87 @@ def test_varlen_max_seqlen_is_only_a_hint_through_the_c_abi():
         assert_close(out, lse, o_ref, l_ref, "varlen with max_seqlen = %d" % max_seqlen)
 
 
+def _colocated_case(len_q, len_k, hq, hkv, seed, causal=True, out_dtype=torch.float32):
+    cq, ck = synth.cu_seqlens_of(len_q), synth.cu_seqlens_of(len_k)
+    tq, tk = int(cq[-1]), int(ck[-1])
+    q, _, _ = synth.qkv(seed, tq, 1, hq, hkv)
+    _, k, v = synth.qkv(seed + 1, 1, tk, hq, hkv)
+    o_ref, l_ref = oracle.colocated(q, k, v, cq, ck, causal=causal)
+    qd, kd, vd = gpu(q, k, v)
+    cqd, ckd = torch.from_numpy(cq).to(DEV), torch.from_numpy(ck).to(DEV)
+    out = torch.full((tq, hq, 128), float("nan"), dtype=out_dtype, device=DEV)     # every row must be written
+    lse = torch.full((hq, tq), float("nan"), dtype=torch.float32, device=DEV)
+    pec.pec_attn_colocated(qd, kd, vd, cqd, ckd, causal, out_dtype=out_dtype, out=out, lse=lse)
+    return (qd, kd, vd, cqd, ckd), (out, lse), (o_ref, l_ref)
+
+
+def test_colocated_batch_matches_oracle():
+    """Short prefills, decode steps of long requests (split into key ranges inside the same launch) and
+    chunks of new tokens behind a cached prefix, in one pec_attn_colocated call."""
+    len_q = [300, 1, 0, 17, 1, 257, 1, 1, 2, 1, 64]
+    len_k = [300, 9000, 40, 500, 1, 257, 4096, 4097, 1, 70000, 64]
+    # prompt | decode over 3 ranges | no query | chunk after a prefix | first token | prompt | decode with exactly one
+    # range (not split) | decode with a 1-key second range | more queries than keys | long decode | prompt
+    for hq, hkv in ((8, 2), (4, 4)):
+        for out_dtype in (torch.float32, torch.bfloat16):
+            _, (out, lse), (o_ref, l_ref) = _colocated_case(len_q, len_k, hq, hkv, 301 + hq, out_dtype=out_dtype)
+            assert_close(out, lse, o_ref, l_ref, "colocated %dq/%dkv %s" % (hq, hkv, out_dtype))
+    # non-causal: every query of a sequence sees all its keys
+    _, (out, lse), (o_ref, l_ref) = _colocated_case([5, 1, 130], [40, 6000, 77], 8, 2, 311, causal=False)
+    assert_close(out, lse, o_ref, l_ref, "colocated non-causal")
+
+
+def test_colocated_batch_is_leak_free_and_reduces_to_the_packed_batch():
+    len_q = [200, 1, 33, 1, 0, 1]
+    len_k = [200, 10000, 700, 5000, 3, 8200]
+    (qd, kd, vd, cqd, ckd), _, _ = _colocated_case(len_q, len_k, 8, 2, 321)
+    # Q = 0: LSE = ln(number of visible keys), exactly the count Eq. 3 sums over, for every row of every sequence
+    _, lse0 = pec.pec_attn_colocated(torch.zeros_like(qd), kd, vd, cqd, ckd, True)
+    want = np.concatenate([np.clip(nk - nq + np.arange(nq) + 1, 0, nk) for nq, nk in zip(len_q, len_k)])
+    got = np.rint(np.exp(lse0.cpu().numpy().astype(np.float64))).astype(np.int64)
+    assert np.array_equal(got, np.tile(want, (8, 1)))
+    # equal query and key offsets: bit-identical to pec_attn_varlen (same kernel, same work items)
+    lengths = [5, 0, 1, 300, 257, 0, 64, 700, 256]
+    cu = torch.from_numpy(synth.cu_seqlens_of(lengths)).to(DEV)
+    q, k, v = gpu(*synth.qkv(331, sum(lengths), sum(lengths), 8, 2))
+    o_c, l_c = pec.pec_attn_colocated(q, k, v, cu, cu, True)
+    o_v, l_v = pec.pec_attn_varlen(q, k, v, cu, max(lengths), True)
+    assert torch.equal(o_c, o_v) and torch.equal(l_c, l_v)
+    # a decode step alone: same as pec_decode_splitkv up to where the bf16 rounding of the weights falls
+    # (different key ranges, hence different softmax references)
+    q1, k1, v1 = gpu(*synth.qkv(341, 1, 20000, 32, 8))
+    one = torch.tensor([0, 1], dtype=torch.int32, device=DEV)
+    kk = torch.tensor([0, 20000], dtype=torch.int32, device=DEV)
+    o_c, l_c = pec.pec_attn_colocated(q1, k1, v1, one, kk, True, out_dtype=torch.float32)
+    o_d, l_d = pec.pec_decode_splitkv(q1, k1, v1, out_dtype=torch.float32)
+    assert (o_c - o_d).abs().max().item() <= 1e-3 and (l_c[:, 0] - l_d).abs().max().item() <= 1e-4
+
+
+def test_full_size_colocated_decode_with_short_prefills_sampled_rows():
+    """The paper's colocation case at full size: 256 log-normal short prompts batched with the decode step of
+    a long request whose cache holds 524,288 tokens (32 query / 8 KV heads), one launch."""
+    hq, hkv = 32, 8
+    short = synth.lognormal_lengths(synth.VARLEN_SEED, synth.VARLEN_N_SHORT)
+    len_q = np.concatenate([short[:100], [1], short[100:]])
+    len_k = np.concatenate([short[:100], [524288], short[100:]])
+    cq, ck = synth.cu_seqlens_of(len_q), synth.cu_seqlens_of(len_k)
+    tq, tk = int(cq[-1]), int(ck[-1])
+    q, _, _ = synth.qkv(351, tq, 1, hq, hkv, device=DEV)
+    _, k, v = synth.qkv(352, 1, tk, hq, hkv, device=DEV)
+    out, lse = pec.pec_attn_colocated(q, k, v, torch.from_numpy(cq).to(DEV), torch.from_numpy(ck).to(DEV), True)
+    # the decode row, all heads
+    b = 100
+    q0, k0 = int(cq[b]), int(ck[b])
+    o_ref, l_ref = oracle.attention(q[q0:q0 + 1].cpu(), k[k0:k0 + 524288].cpu(), v[k0:k0 + 524288].cpu(), causal=False)
+    assert_close(out[q0:q0 + 1], lse[:, q0:q0 + 1], o_ref, l_ref, "colocated decode row")
+    # sampled rows of a few short prompts next to it and elsewhere
+    for b in (99, 101, 3, 255):
+        q0, k0, n = int(cq[b]), int(ck[b]), int(len_q[b])
+        rows = synth.sample_rows(b, n, boundaries=(256,) if n > 300 else (), n_random=6, edge=2)
+        _sampled_check(q[q0:q0 + n], k[k0:k0 + n], v[k0:k0 + n], out[q0:q0 + n], lse[:, q0:q0 + n], 0, rows,
+                       heads=b % hkv, what="colocated short prompt %d (len %d)" % (b, n))
+
+
 def _sampled_check(qd, kd, vd, out, lse, q_off, rows, heads=None, what=""):
     """Oracle on sampled rows against the full key range (rows are independent in Eq. 2-3)."""
     g = qd.shape[1] // kd.shape[1]

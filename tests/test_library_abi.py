@@ -80,6 +80,16 @@ def test_argument_validation_happens_on_the_host(lib):
     assert lib.pec_varlen_workspace_bytes(4, 1000) > 0
     assert lib.pec_attn_varlen(ctypes.byref(ok), fake, fake, fake, fake, 4, 1000, 512, 1, fake, fake, None, 0, None) == -4
     assert lib.pec_attn_varlen(ctypes.byref(ok), fake, fake, fake, fake, 0, 0, 0, 1, fake, fake, None, 0, None) == 0
+    # colocated batch: workspace, null offsets, the plain kernel is refused, empty batch is a no-op
+    need = lib.pec_colocated_workspace_bytes(ctypes.byref(ok), 4, 1000, 50000)
+    assert need >= (50000 // 4096 + 4) * 8 * 129 * 4
+    coloc = lambda shp, cq=fake, ws=fake, nbytes=1 << 40, batch=4: lib.pec_attn_colocated(  # noqa: E731
+        ctypes.byref(shp), fake, fake, fake, cq, fake, batch, 1000, 50000, 1, fake, fake, ws, nbytes, None)
+    assert coloc(ok, nbytes=need - 1) == -4
+    assert coloc(ok, ws=None) == -4
+    assert coloc(ok, cq=None) == -1
+    assert coloc(S(8, 2, 128, 0, 0.0, binding.PEC_FLAG_SIMPLE_KERNEL)) == -2
+    assert coloc(ok, batch=0) == 0
 
 
 def test_binding_refuses_cpu_tensors(lib):
