@@ -35,7 +35,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pec_oracle.c")
-_LIB = os.path.join(_HERE, "libpec_oracle.so")
+# PEC_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (the process then has to run with libasan preloaded; see
+# tests/test_oracle_sanitizers.py).
+_SANITIZE = os.environ.get("PEC_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libpec_oracle_san.so" if _SANITIZE else "libpec_oracle.so")
 _lib = None
 
 
@@ -43,9 +47,9 @@ def build(force: bool = False) -> str:
     """Compile pec_oracle.c with gcc (OpenMP) next to its source."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", tmp, _SRC, "-lm"]
-        )
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=undefined"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
