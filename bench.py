@@ -78,6 +78,23 @@ def mfma_probe(torch, pec, dev, iters=20000):
     return res
 
 
+def hbm_read_probe(torch, pec, dev, gib=2):
+    """Streaming read of a buffer far larger than the caches: the read bandwidth the memory system delivers."""
+    buf = torch.empty(gib << 28, dtype=torch.float32, device=dev).normal_()
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for _ in range(2):
+        pec.pec_hbm_read_probe(buf, sink)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        pec.pec_hbm_read_probe(buf, sink)
+    ev1.record()
+    torch.cuda.synchronize()
+    gbs = 5.0 * buf.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    return {"read_gbs": round(gbs, 1), "what": "streaming read of %d GiB, 8 x 16-byte loads in flight per thread" % gib}
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of this workload
     (line 'traffic_bytes_per_launch: N' in profiles/<kernel>_<workload>_hbm_traffic.md); None if there is none."""
@@ -408,6 +425,10 @@ def bench_ulysses(args, torch, np, pec, synth, dev):
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                      "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::ulysses_layout_kernel"},
     }
+    del y, z
+    probe = hbm_read_probe(torch, pec, dev)
+    result["hbm_read_probe"] = probe
+    result["pct_of_measured_read_bandwidth"] = round(100.0 * gbs / probe["read_gbs"], 2)
     print(json.dumps(result), flush=True)
     return 0
 
@@ -442,6 +463,9 @@ def bench_decode(args, torch, np, pec, synth, dev):
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                      "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "pec::decode_kernel + pec::combine_splits_kernel"},
     }
+    probe = hbm_read_probe(torch, pec, dev)
+    result["hbm_read_probe"] = probe
+    result["pct_of_measured_read_bandwidth"] = round(100.0 * gbs / probe["read_gbs"], 2)
     print(json.dumps(result), flush=True)
     return 0
 

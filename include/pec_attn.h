@@ -289,6 +289,14 @@ int pec_sp_select_strategy(const pec_sp_model_t* model, pec_sp_choice_t* choice)
 int64_t pec_mfma_probe(const void* operands, size_t operand_bytes, int32_t iters, float* sink, size_t sink_floats,
                        void* stream);
 
+/*
+ * Measurement aid, not part of the method: one streaming read of `bytes` bytes (a multiple of 16) at
+ * `src` (DEVICE), eight 16-byte loads in flight per thread, 32 workgroups per compute unit; `sink`
+ * (DEVICE, 4 bytes) is only there so that the loads count as used.  Timed by the caller, it gives the
+ * read bandwidth the memory system delivers, the ceiling of the HBM-bound kernels of this library.
+ */
+int pec_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
 const char* pec_status_string(int status);
 
 #ifdef __cplusplus

@@ -22,7 +22,7 @@ KERNEL_NAMES = {0: "pec::fwd_il_kernel", PEC_FLAG_SIMPLE_KERNEL: "pec::fwd_simpl
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
     "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
-    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_mfma_probe", "pec_attn_colocated", "pec_colocated_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
+    "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_mfma_probe", "pec_hbm_read_probe", "pec_attn_colocated", "pec_colocated_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
 )
 
 
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.pec_attn_colocated.restype = ci
         L.pec_colocated_workspace_bytes.argtypes = [sp, i32, i64, i64]
         L.pec_colocated_workspace_bytes.restype = sz
+        L.pec_hbm_read_probe.argtypes = [vp, sz, vp, vp]
+        L.pec_hbm_read_probe.restype = ci
         L.pec_mfma_probe.argtypes = [vp, sz, i32, vp, sz, vp]
         L.pec_mfma_probe.restype = i64
         L.pec_status_string.argtypes = [ci]
@@ -329,6 +331,12 @@ def pec_attn_colocated(q, k, v, cu_seqlens_q, cu_seqlens_k, causal: bool = True,
                                     batch, total_q, total_k, int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace),
                                     workspace.numel(), _stream(stream)))
     return out, lse
+
+
+def pec_hbm_read_probe(src, sink, stream=None) -> None:
+    """One streaming read of the whole tensor `src` (any dtype, contiguous, on the GPU)."""
+    _check("pec_hbm_read_probe", lib().pec_hbm_read_probe(_ptr(src), (src.numel() * src.element_size()) // 16 * 16,
+                                                          _ptr(sink), _stream(stream)))
 
 
 def pec_mfma_probe(operands, iters: int, sink, stream=None) -> int:

@@ -2,10 +2,10 @@
 // range of keys on its own, no workgroup barrier anywhere.
 //
 // The step is HBM-bound (K and V are read once, 512 bytes per key and KV head, against 1 Kflop),
-// so the design goal is bytes in flight: each wavefront owns a private two-stage LDS ring of
-// 32-key K and V tiles filled by direct global->LDS loads, i.e. up to 2 x 16 KiB outstanding per
-// wavefront, 128 KiB per compute unit (4 wavefronts), enough to cover the memory latency at the
-// full HBM rate.  The g query heads that share a KV head are the 32 "query columns" of the same
+// so the design goal is bytes in flight: each wavefront owns private LDS rings of 32-key tiles filled
+// by direct global->LDS loads, two stages for K and three for V (all of the 160 KiB of LDS: V is
+// consumed last in a tile, so the extra stage goes to it), i.e. up to 40 KiB outstanding per
+// wavefront and 160 KiB per compute unit (4 wavefronts) to cover the memory latency at the HBM rate.  The g query heads that share a KV head are the 32 "query columns" of the same
 // transposed-score MFMA scheme as the prefill kernels (columns >= g carry zeros): the matrix
 // pipe is mostly idle and does not matter here.
 //
@@ -35,10 +35,11 @@ struct DecodeParams {
 constexpr int kDecTile = 32;                          // keys per tile
 constexpr int kDecTileBytes = kDecTile * kRowBytes;   // 8 KiB for K, 8 KiB for V
 constexpr int kDecWaves = 4;
+constexpr int kDecKStages = 2, kDecVStages = 3;      // ring depths: K(j) is requested two tiles ahead, V(j) three
 
 __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const DecodeParams p) {
-    // [wave][stage][K, V]
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[kDecWaves][2][2][kDecTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_k[kDecWaves][kDecKStages][kDecTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_v[kDecWaves][kDecVStages][kDecTileBytes];
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -85,24 +86,24 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const DecodePara
                      : "v"(voff), "s"(sbase), "s"(lds_addr)
                      : "memory", "m0");
     };
-    auto issue_tile = [&](int tile) {
+    auto issue_half = [&](const unsigned char* base, bool is_v, int tile, unsigned char* stage) {
         if (tile >= n_tiles) return;
-        const int stage = tile & 1;
         const int key0 = tile * kDecTile;
         const int last = len - 1 - key0;   // last valid row of this tile (>= 0)
-        const unsigned char* kt = kbase + (int64_t)key0 * kv_stride_b;
-        const unsigned char* vt = vbase + (int64_t)key0 * kv_stride_b;
-        const uint32_t lk = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds[wave][stage][0];
-        const uint32_t lv = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds[wave][stage][1];
+        const unsigned char* tb = base + (int64_t)key0 * kv_stride_b;
+        const uint32_t l0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)stage;
 #pragma unroll
         for (int i = 0; i < kDecTile / 4; ++i) {
             const int key = 4 * i + ld_row;
             const uint32_t row_off = (uint32_t)min(key, last) * kv_stride_b;
-            dma16(kt, row_off + (uint32_t)(ld_pos ^ (key & 15)) * 16u, lk + i * 1024);
-            dma16(vt, row_off + (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u, lv + i * 1024);
+            const uint32_t col = is_v ? (uint32_t)((((ld_pos >> 2) ^ (key & 3)) << 2) | (ld_pos & 3)) * 16u
+                                      : (uint32_t)(ld_pos ^ (key & 15)) * 16u;
+            dma16(tb, row_off + col, l0 + i * 1024);
         }
     };
-    constexpr int kLoadsPerTile = 2 * (kDecTile / 4);   // 16 load instructions per tile and wavefront
+    auto issue_k = [&](int tile) { issue_half(kbase, false, tile, lds_k[wave][tile % kDecKStages]); };
+    auto issue_v = [&](int tile) { issue_half(vbase, true, tile, lds_v[wave][tile % kDecVStages]); };
+    constexpr int kLoadsPerHalf = kDecTile / 4;   // 8 load instructions per K or V tile and wavefront
 
     // ---- LDS operand offsets
     uint32_t k_off[8];
@@ -123,16 +124,22 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const DecodePara
     float m_run = -INFINITY, l_run = 0.f;
     const float sl2 = p.scale_log2;
 
-    issue_tile(0);
-    issue_tile(1);
+    // Issue order: K(0) V(0) K(1) V(1) V(2), then per tile j: K(j+2) V(j+3).  Loads retire in order, so
+    // when tile j starts the requests younger than K(j) and V(j) are V(j+1) | K(j+1) V(j+2): 24 of them
+    // in the steady state, fewer at the end of the range (tiles past the end are not requested).
+    issue_k(0);
+    issue_v(0);
+    issue_k(1);
+    issue_v(1);
+    issue_v(2);
+    static_assert(kLoadsPerHalf == 8 && kDecKStages == 2 && kDecVStages == 3, "the vmcnt immediates below assume this");
     for (int j = 0; j < n_tiles; ++j) {
-        // tile j has landed when at most the loads of tile j + 1 are outstanding (loads retire in order)
-        if (j + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
-        static_assert(kLoadsPerTile == 16, "the vmcnt immediate above assumes 16 loads per tile");
-        asm volatile("" ::: "memory");
-        const unsigned char* kst = lds[wave][j & 1][0];
-        const unsigned char* vst = lds[wave][j & 1][1];
+        const int left = n_tiles - 1 - j;   // tiles after this one
+        if (left >= 2) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");        // V(j+1) K(j+1) V(j+2)
+        else if (left == 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // V(j+1) K(j+1)
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const unsigned char* kst = lds_k[wave][j % kDecKStages];
+        const unsigned char* vst = lds_v[wave][j % kDecVStages];
 
         // S^T = K Q^T for 32 keys
         f32x16 s;
@@ -194,9 +201,10 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const DecodePara
                 const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pp[ks], o[dt], 0, 0, 0);
             }
-        // the LDS reads of this stage are consumed (the MFMAs above needed them): refill it
+        // the LDS reads of this tile's stages are consumed (the MFMAs above needed them): refill them
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        issue_tile(j + 2);
+        issue_k(j + 2);
+        issue_v(j + 3);
     }
 
     // ---- partial result of this range

@@ -15,7 +15,7 @@
 #include "decode_kernel.hpp"
 #include "fwd_kernel.hpp"
 #include "fwd_kernel_il.hpp"
-#include "mfma_probe.hpp"
+#include "probes.hpp"
 
 namespace {
 
@@ -684,6 +684,14 @@ int64_t pec_mfma_probe(const void* operands, size_t operand_bytes, int32_t iters
     if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
     // flop of the launch: every MFMA is 32 x 32 x 16 multiply-adds
     return (int64_t)grid * kProbeWaves * iters * kProbeMfmaPerIter * (2LL * 32 * 32 * 16);
+}
+
+int pec_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink || bytes < 16) return PEC_ERR_INVALID_ARGUMENT;
+    if (misaligned(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return PEC_ERR_MISALIGNED;
+    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(compute_units() * 32), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+    return hipGetLastError() == hipSuccess ? PEC_OK : PEC_ERR_HIP;
 }
 
 const char* pec_status_string(int status) {
