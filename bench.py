@@ -95,6 +95,31 @@ def hbm_read_probe(torch, pec, dev, gib=2):
     return {"read_gbs": round(gbs, 1), "what": "streaming read of %d GiB, 8 x 16-byte loads in flight per thread" % gib}
 
 
+def item_fit(torch, np, pec, synth, dev):
+    """Time of an unmasked pec_attn_chunk_merge launch (32 q / 8 kv heads, fp32 running state in and out) as
+    T = L + n (o + tiles t): n work items per compute unit (256 query rows of one head each), `tiles` key
+    tiles of 64 per item.  Least-squares fit of L (per launch), o (per work item) and t (per tile step)."""
+    q, _, _ = synth.qkv(1, 32768, 16, 32, 8, device=dev)
+    _, k, v = synth.qkv(2, 16, 16384, 32, 8, device=dev)
+    oacc = torch.zeros(32768, 32, 128, dtype=torch.float32, device=dev)
+    lse = torch.zeros(32, 32768, dtype=torch.float32, device=dev)
+    rows, ys = [], []
+    for sq in (2048, 4096, 8192, 16384, 32768):
+        for sk in (2048, 4096, 8192, 16384):
+            if sq * sk > 8192 * 32768:
+                continue
+            qq, kk, vv, oa, ll = q[:sq], k[:sk], v[:sk], oacc[:sq], lse[:, :sq].contiguous()
+            _, ev = timed_steps(torch, lambda: pec.pec_attn_chunk_merge(qq, kk, vv, 1 << 20, 0, oa, ll, True), 10, 3)
+            n, tiles = sq // 2048, sk // 64
+            rows.append([1.0, n, n * tiles])
+            ys.append(1e3 * sum(ev) / len(ev))
+    sol = np.linalg.lstsq(np.array(rows), np.array(ys), rcond=None)[0]
+    resid = float(np.abs(np.array(rows) @ sol - np.array(ys)).max())
+    return {"per_launch_us": round(float(sol[0]), 2), "per_work_item_us": round(float(sol[1]), 2),
+            "per_tile_step_us": round(float(sol[2]), 4), "max_residual_us": round(resid, 1), "launches_fitted": len(ys),
+            "asymptotic_tflops": round(512.0 * 32 * 256 * 64 * 256 / 32 / (float(sol[2]) * 1e-6) / 1e12, 1)}
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of this workload
     (line 'traffic_bytes_per_launch: N' in profiles/<kernel>_<workload>_hbm_traffic.md); None if there is none."""
@@ -123,6 +148,9 @@ def parse_args():
     ap.add_argument("--decode-splits", type=int, default=0, help="key ranges per KV head for --workload decode_512k (0: library default)")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="only measure the bare MFMA rate (constant and N(0,1) operands) and print it as one JSON line")
+    ap.add_argument("--item-fit", action="store_true",
+                    help="only fit launch / work-item / tile-step costs of the attention kernel from unmasked launches of "
+                         "different shapes (32 q / 8 kv heads) and print them as one JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three 1 GiB device-to-device copies (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -154,6 +182,9 @@ def main():
     pec.lib()  # fails loudly when the HIP library has not been built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.item_fit:
+        print(json.dumps({"item_fit": item_fit(torch, np, pec, synth, dev)}), flush=True)
+        return 0
     if args.mfma_probe:
         print(json.dumps({"mfma_probe": mfma_probe(torch, pec, dev), "nominal_peak_tflops": PEAK_BF16_TFLOPS}), flush=True)
         return 0
