@@ -388,6 +388,41 @@ def test_full_size_colocated_decode_with_short_prefills_sampled_rows():
                        heads=b % hkv, what="colocated short prompt %d (len %d)" % (b, n))
 
 
+def test_many_sequences_fill_the_work_lists_without_gaps_or_leaks():
+    """More sequences than the work-list builders have threads (1024), many of them empty or one token long:
+    the Q = 0 count of visible keys must be right for every row of every sequence (a dropped, duplicated or
+    misplaced work item shows as a wrong or unwritten count), packed and colocated."""
+    rng = np.random.default_rng(77)
+    n = 2600
+    lens = rng.integers(0, 40, size=n)
+    lens[rng.integers(0, n, size=40)] = rng.integers(250, 600, size=40)       # some spill into a second / third query tile
+    cu = synth.cu_seqlens_of(lens)
+    t, hq, hkv = int(cu[-1]), 4, 2
+    _, k, v = synth.qkv(401, 1, t, hq, hkv)
+    q0 = torch.zeros(t, hq, 128, dtype=torch.bfloat16, device=DEV)
+    cud = torch.from_numpy(cu).to(DEV)
+    lse = torch.full((hq, t), float("nan"), dtype=torch.float32, device=DEV)
+    pec.pec_attn_varlen(q0, k.to(DEV), v.to(DEV), cud, int(lens.max()), True, lse=lse)
+    pos = np.concatenate([np.arange(m) for m in lens])
+    got = np.rint(np.exp(lse.cpu().numpy().astype(np.float64))).astype(np.int64)
+    assert np.array_equal(got, np.tile(pos + 1, (hq, 1)))
+    # colocated: the same prompts, every fifth sequence replaced by a decode step over a cache of its own
+    len_q, len_k = lens.copy(), lens.copy()
+    dec = np.arange(0, n, 5)
+    len_q[dec] = 1
+    len_k[dec] = rng.integers(1, 9000, size=dec.size)
+    cq, ck = synth.cu_seqlens_of(len_q), synth.cu_seqlens_of(len_k)
+    tq, tk = int(cq[-1]), int(ck[-1])
+    _, k2, v2 = synth.qkv(402, 1, tk, hq, hkv)
+    q0 = torch.zeros(tq, hq, 128, dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((hq, tq), float("nan"), dtype=torch.float32, device=DEV)
+    pec.pec_attn_colocated(q0, k2.to(DEV), v2.to(DEV), torch.from_numpy(cq).to(DEV), torch.from_numpy(ck).to(DEV), True,
+                           lse=lse)
+    want = np.concatenate([np.clip(nk - nq + np.arange(nq) + 1, 0, nk) for nq, nk in zip(len_q, len_k)])
+    got = np.rint(np.exp(lse.cpu().numpy().astype(np.float64))).astype(np.int64)
+    assert np.array_equal(got, np.tile(want, (hq, 1)))
+
+
 def _sampled_check(qd, kd, vd, out, lse, q_off, rows, heads=None, what=""):
     """Oracle on sampled rows against the full key range (rows are independent in Eq. 2-3)."""
     g = qd.shape[1] // kd.shape[1]
