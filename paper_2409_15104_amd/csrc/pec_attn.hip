@@ -610,6 +610,7 @@ int pec_attn_colocated(const pec_shape_t* shape, const void* q, const void* k, c
     float scale;
     if (int rc = check_shape(shape, &scale)) return rc;
     if (shape->flags & PEC_FLAG_SIMPLE_KERNEL) return PEC_ERR_UNSUPPORTED;   // the plain kernel knows no key ranges
+    if (shape->n_q_heads / shape->n_kv_heads > 256) return PEC_ERR_UNSUPPORTED;   // a KV group's heads are the rows of one query tile
     if (batch < 0 || total_q < 0 || total_k < 0) return PEC_ERR_INVALID_ARGUMENT;
     if (total_q > kMaxRows || total_k > kMaxRows) return PEC_ERR_UNSUPPORTED;
     if (batch == 0 || total_q == 0) return PEC_OK;
@@ -646,7 +647,6 @@ int pec_attn_colocated(const pec_shape_t* shape, const void* q, const void* k, c
     p.n_q_heads = shape->n_q_heads;
     p.n_kv_heads = shape->n_kv_heads;
     p.group = shape->n_q_heads / shape->n_kv_heads;
-    if (p.group > 256) return PEC_ERR_UNSUPPORTED;   // the heads of a KV group are the rows of one query tile
     p.n_items = (int32_t)L.cap_items;
     p.out_f32 = shape->out_dtype == PEC_F32;
     p.scale_log2 = scale * kLog2e;
