@@ -62,10 +62,11 @@ typedef struct {
 enum {
     PEC_FLAG_SIMPLE_KERNEL = 1u,     /* run the plain, unpipelined attention kernel (exact running maximum, no
                                         persistence) instead of the default one: a cross-check, several times slower */
-    PEC_FLAG_SP_SEPARATE_MERGE = 2u, /* pec_sp_prefill: pec_attn_chunk -> fp32 partial -> pec_attn_merge per ring step,
-                                        instead of the default merge fused into the next step's kernel */
-    PEC_FLAG_SP_SINGLE_LAUNCH = 4u   /* pec_sp_prefill: one launch sweeping all segments with the running state in
-                                        registers (no point between segments where a scheduler could stop) */
+    PEC_FLAG_SP_SEPARATE_MERGE = 2u, /* pec_sp_prefill: one launch per ring step, pec_attn_chunk -> fp32 partial ->
+                                        pec_attn_merge, instead of the default single sweep */
+    PEC_FLAG_SP_STEP_LAUNCHES = 4u   /* pec_sp_prefill: one launch per ring step with the merge fused into the kernel
+                                        (what issuing pec_sp_prefill_step back to back does), instead of the
+                                        default single sweep */
 };
 
 /*
@@ -110,21 +111,54 @@ int pec_finalize(const pec_shape_t* shape, const float* o_f32, void* o_bf16, int
  * One ring member's whole prefill on one GPU: the query segment q [s_q, Hq, 128]
  * at global offset q_off attends over k/v [s_kv, Hkv, 128] (global positions
  * 0..s_kv-1) cut into contiguous segments of `chunk` tokens (the last may be
- * short).  Segments are visited in ring order starting from the member's own,
- * (r - t) mod P for step t with r = q_off / chunk; under the causal mask segments
- * wholly in the future are skipped.  Each step is a separate kernel launch, so a
- * scheduler can stop between two steps (section "Preemption of Long-Request
- * Prefill").  By default step t > 0 folds its segment into the running fp32 pair
- * inside the kernel (pec_attn_chunk_merge); PEC_FLAG_SP_SEPARATE_MERGE and
- * PEC_FLAG_SP_SINGLE_LAUNCH select the two other ways of combining the partials.
+ * short); under the causal mask segments wholly in the future are skipped.
+ * By default ONE launch sweeps all visible segments in position order, the running
+ * (O, LSE) of every query tile staying in registers from segment to segment; this
+ * call cannot be stopped half way (pec_sp_prefill_resumable and pec_sp_prefill_step
+ * can).  PEC_FLAG_SP_STEP_LAUNCHES and PEC_FLAG_SP_SEPARATE_MERGE instead launch
+ * once per ring step, in ring order starting from the member's own segment,
+ * (r - t) mod P for step t with r = q_off / chunk, the running fp32 pair going
+ * through the workspace between steps (merged inside the next step's kernel, or by
+ * pec_attn_merge).  All three give the same result up to fp32 rounding order.
  *   out [s_q, Hq, 128] in shape->out_dtype, lse [Hq, s_q].
  * workspace: device scratch of at least pec_sp_workspace_bytes() bytes, 16-byte
- * aligned; contents undefined on return.
+ * aligned; contents undefined on return (not used by the default sweep).
  */
 int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const void* v,
                    int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk, int causal,
                    void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
+
+/*
+ * The sweep of pec_sp_prefill as a launch that a scheduler can stop between two key
+ * segments and continue later (section "Preemption of Long-Request Prefill": the
+ * long prefill yields at operation granularity and only the intermediate data of
+ * the interrupted operation is kept).  Every workgroup looks at *stop shortly
+ * before each segment boundary of the query tile it is working on; once it reads a
+ * nonzero value it finishes the segment in hand, puts the tile's running fp32 pair
+ * and the number of segments done into the workspace, and takes no further tile.
+ * A later call with resume = 1 and the same arguments and workspace continues every
+ * tile from where it stopped; *pending is then the number of query tiles x heads
+ * that have not yet seen their last key (0: out and lse are complete).  A launch
+ * always takes each workgroup's first unfinished tile through at least one more
+ * segment, so repeated calls end even if *stop stays set.
+ *   stop    : int32 the GPU can read while the kernel runs (device memory written from
+ *             another stream, or pinned host memory); NULL = never stop.  Segments
+ *             shorter than 1024 keys, and query tiles with fewer than 256 rows, are
+ *             only left between tiles, not between segments.
+ *   pending : DEVICE int32, written by the call (resume = 0 sets it to the tile count).
+ *   resume  : 0 starts from the first segment and ignores the workspace contents.
+ *   chunk   : a multiple of 64 (PEC_ERR_UNSUPPORTED otherwise).
+ *   workspace: pec_sp_resumable_workspace_bytes() bytes, 16-byte aligned; holds the
+ *             state between calls (the caller may copy it away and back); lse holds
+ *             the running LSE of unfinished tiles meanwhile.
+ * PEC_FLAG_SIMPLE_KERNEL is refused (PEC_ERR_UNSUPPORTED).
+ */
+int pec_sp_prefill_resumable(const pec_shape_t* shape, const void* q, const void* k, const void* v,
+                             int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk, int causal,
+                             void* out, float* lse, void* workspace, size_t workspace_bytes,
+                             const int32_t* stop, int32_t* pending, int resume, void* stream);
+size_t pec_sp_resumable_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
 
 /*
  * The same prefill one ring step at a time, for a scheduler that pauses a long prefill between
@@ -137,7 +171,7 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  *   order, each exactly once; anything may run on the GPU, and the state may be copied away and
  *   back, between two steps.  If out_final is not NULL on the last step the result is written
  *   there in shape->out_dtype (and o_acc is then left unchanged); lse_acc always ends as the LSE.
- * Issuing all steps back to back is what pec_sp_prefill does by default.
+ * Issuing all steps back to back is what pec_sp_prefill does with PEC_FLAG_SP_STEP_LAUNCHES.
  */
 int64_t pec_sp_prefill_num_steps(const pec_shape_t* shape, int64_t s_q, int64_t q_off, int64_t s_kv,
                                  int64_t chunk, int causal);

@@ -16,12 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpec_attn.so")
 
 PEC_BF16, PEC_F32 = 0, 1
-PEC_FLAG_SIMPLE_KERNEL, PEC_FLAG_SP_SEPARATE_MERGE, PEC_FLAG_SP_SINGLE_LAUNCH = 1, 2, 4
+PEC_FLAG_SIMPLE_KERNEL, PEC_FLAG_SP_SEPARATE_MERGE, PEC_FLAG_SP_STEP_LAUNCHES = 1, 2, 4
 KERNEL_NAMES = {0: "pec::fwd_il_kernel", PEC_FLAG_SIMPLE_KERNEL: "pec::fwd_simple_kernel"}
 
 EXPORTS = (
     "pec_attn_chunk", "pec_attn_chunk_merge", "pec_attn_merge", "pec_finalize", "pec_sp_prefill",
-    "pec_sp_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
+    "pec_sp_workspace_bytes", "pec_sp_prefill_resumable", "pec_sp_resumable_workspace_bytes", "pec_sp_prefill_num_steps", "pec_sp_prefill_step", "pec_decode_splitkv", "pec_ulysses_layout", "pec_sp_select_strategy", "pec_decode_default_splits",
     "pec_decode_workspace_bytes", "pec_decode_splitkv_static", "pec_mfma_probe", "pec_hbm_read_probe", "pec_attn_colocated", "pec_colocated_workspace_bytes", "pec_attn_varlen", "pec_varlen_workspace_bytes", "pec_status_string",
 )
 
@@ -70,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.pec_sp_prefill.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp, sz, vp]
         L.pec_sp_workspace_bytes.argtypes = [sp, i64]
         L.pec_sp_workspace_bytes.restype = sz
+        L.pec_sp_prefill_resumable.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp, sz, vp, vp, ci, vp]
+        L.pec_sp_resumable_workspace_bytes.argtypes = [sp, i64]
+        L.pec_sp_resumable_workspace_bytes.restype = sz
         L.pec_sp_prefill_num_steps.argtypes = [sp, i64, i64, i64, i64, ci]
         L.pec_sp_prefill_num_steps.restype = i64
         L.pec_sp_prefill_step.argtypes = [sp, vp, vp, vp, i64, i64, i64, i64, ci, i64, vp, vp, vp, vp]
@@ -217,6 +220,31 @@ def pec_sp_prefill(q, k, v, q_off: int, chunk: int, causal: bool = True, out_dty
                                 int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(),
                                 _stream(stream)))
     return out, lse
+
+
+def pec_sp_resumable_workspace_bytes(q, k) -> int:
+    shp = _shape(q, k, torch.bfloat16, 0.0)
+    return int(lib().pec_sp_resumable_workspace_bytes(ctypes.byref(shp), q.shape[0]))
+
+
+def pec_sp_prefill_resumable(q, k, v, q_off: int, chunk: int, out, lse, workspace, pending, stop=None, resume: bool = False,
+                             causal: bool = True, scale: float = 0.0, flags: int = 0, stream=None):
+    """One launch of the stoppable sweep; `stop` (int32 tensor the GPU can read, or None) and `pending` (device int32
+    tensor of one element) as in the C header.  Returns nothing: read `pending` to learn whether out / lse are complete."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    _require(lse, torch.float32, "lse")
+    _require(pending, torch.int32, "pending")
+    shp = _shape(q, k, out.dtype, scale, flags)
+    stop_ptr = None
+    if stop is not None:
+        if stop.dtype != torch.int32:
+            raise ValueError("stop must be an int32 tensor")
+        stop_ptr = ctypes.c_void_p(stop.data_ptr())      # device memory or pinned host memory
+    _check("pec_sp_prefill_resumable",
+           lib().pec_sp_prefill_resumable(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), q.shape[0], int(q_off), k.shape[0],
+                                          int(chunk), int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace),
+                                          workspace.numel(), stop_ptr, _ptr(pending), int(bool(resume)), _stream(stream)))
 
 
 def pec_sp_prefill_num_steps(q, k, q_off: int, chunk: int, causal: bool = True) -> int:

@@ -342,4 +342,11 @@ __global__ __launch_bounds__(1024) void build_colocated_worklist_kernel(
     }
 }
 
+// Start of a resumable sweep: no item has a segment behind it, all of them are pending.
+__global__ void sweep_init_kernel(int32_t* progress, int64_t n_items, int32_t* pending) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_items; i += (int64_t)gridDim.x * blockDim.x)
+        progress[i] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *pending = (int32_t)n_items;
+}
+
 }  // namespace pec

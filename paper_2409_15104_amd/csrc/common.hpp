@@ -43,6 +43,8 @@ struct WorkItem {   // one (sequence, query tile) of a packed batch; in a coloca
     int32_t qtile;
 };
 
+constexpr int32_t kSweepDone = 0x7fffffff;
+
 struct FwdParams {
     const __bf16* q;
     const __bf16* k;
@@ -82,6 +84,15 @@ struct FwdParams {
     float* part_lse;            // [slots][n_q_heads]
     int32_t total_k;            // rows of the packed k / v arrays
     int32_t coloc_range_len;    // keys per range, a multiple of 64
+    // resumable sweep (dense mode, progress != null; fwd_il_kernel only): work item i has finished its first
+    // progress[i] key segments of seg_tiles tiles each (kSweepDone: all of them) and continues from there, its
+    // running pair in acc_in / lse_in.  A nonzero *stop makes a workgroup end the item in hand at the next
+    // segment boundary (state to acc_out / lse, progress updated) and take no further item; an item that gets
+    // through its last key writes out / lse and takes one off *pending.
+    int32_t* progress;
+    int32_t* pending;
+    const int32_t* stop;
+    int32_t seg_tiles;
 };
 
 __device__ __forceinline__ uint32_t k_lds_off(int key, int chunk16) {

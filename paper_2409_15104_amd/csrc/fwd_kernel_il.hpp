@@ -58,7 +58,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     // of the tile loop is then "lane offset + 16-bit immediate".  (Separate arrays are placed by the
     // compiler in an order of its own; a stage that lands above 64 KiB needs its address in a register,
     // and the tile loop has none to spare.)
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_all[4 * kTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_all[4 * kTileBytes + 256];
     unsigned char* const lds_k0 = lds_all;
     unsigned char* const lds_k1 = lds_all + kTileBytes;
     unsigned char* const lds_v0 = lds_all + 2 * kTileBytes;
@@ -73,6 +73,22 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_slots = (int)(gridDim.x >> 3);
     const int slot = (int)(blockIdx.x >> 3);
+    // 64 copies of the stop word of a resumable sweep, brought in by wavefront 0 with a tile-style load
+    const uint32_t lds_stop = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_all + 4 * kTileBytes;
+    auto request_stop_word = [&]() {   // lands with the tile loads; visible to everyone after the next barrier
+        if (wave == 0) {
+            uint32_t zero;
+            asm volatile("v_mov_b32 %0, 0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 sc0 sc1"
+                         : "=&v"(zero)
+                         : "s"(p.stop), "s"(lds_stop)
+                         : "memory", "m0");
+        }
+    };
+    auto read_stop_word = [&]() -> int {
+        const int v = *reinterpret_cast<const volatile int*>(lds_all + 4 * kTileBytes);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+    bool first_item = true;   // of this workgroup in this launch: it is never abandoned before its first segment
     for (int64_t round0 = 0; round0 < per_xcd; round0 += n_slots) {
     // Lane-derived values are recomputed for every work item (the empty asm hides that they are
     // loop invariant): hoisted out of this loop they would stay live through the tile loop, which
@@ -99,6 +115,9 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     void* out_ptr = p.out;
     float* lse_ptr = p.lse;
     int out_f32 = p.out_f32;
+    const float* acc_in = p.acc_in;
+    float* acc_out = p.acc_out;
+    int seg_done = 0;          // resumable sweep: key segments this item has behind it
     if (p.cu_seqlens) {
         if (item >= *p.n_work) continue;
         const WorkItem w = p.work[item];
@@ -144,6 +163,14 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         q_off0 = (int64_t)head * (p.q_head_stride ? p.q_head_stride : kHeadDim);
         o_off0 = q_off0;
         lse_off0 = (int64_t)head * p.lse_stride;
+        if (p.progress) {           // resumable sweep: continue behind the segments already folded in
+            seg_done = p.progress[logical];
+            if (seg_done == kSweepDone) continue;
+            if (seg_done == 0) acc_in = nullptr;
+            kv_tok0 = (int64_t)seg_done * p.seg_tiles * kBN;
+            sk -= (int)kv_tok0;
+            delta -= (int)kv_tok0;
+        }
         if (p.kv_split_len > 0) {   // the work item is a key range; all of it is visible (decode)
             qt = 0;
             kv_tok0 = (int64_t)item * p.kv_split_len;
@@ -159,7 +186,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     const int blk_last = min(sq, row0 + BM) - 1;
     int kv_end = sk;
     if (causal) kv_end = max(0, min(sk, blk_last + delta + 1));
-    const int n_tiles = (kv_end + kBN - 1) / kBN;
+    int n_tiles = (kv_end + kBN - 1) / kBN;
 
     // runs of tiles for this wavefront: [0, n_full) need no mask, [n_full, n_act) do,
     // [n_act, n_tiles) lie wholly after its rows (causal only)
@@ -199,14 +226,14 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-    if (p.acc_in) {
+    if (acc_in) {
         const int row = rw0 + l32;
         if (row < sq) {
             const float lin = p.lse_in[lse_off0 + row];
             if (lin != -INFINITY) {
                 m_run = lin * kLog2e;
                 l_run = hl == 0 ? 1.f : 0.f;
-                const float* arow = p.acc_in + o_off0 + row * q_stride + 4 * hl;
+                const float* arow = acc_in + o_off0 + row * q_stride + 4 * hl;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -519,7 +546,11 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     issue_k(0, lds_k0);
     issue_k(1, lds_k1);
     issue_v(0, lds_v1);
+    const bool may_stop = p.stop != nullptr;
+    if (may_stop && !first_item) request_stop_word();
     end_of_iteration();
+    if (may_stop && !first_item && read_stop_word() != 0) return;   // nothing of this item has been touched
+    first_item = false;
     if (n_act > 0) {
         qk_mfma(s_a, lds_k0);
         row_max(T{}, s_a, 0);
@@ -540,10 +571,45 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     // ---- schedule: every wavefront passes one barrier per tile.  Iteration j needs the mask
     // for tile j + 1, so the unmasked run ends one tile early; it is taken in whole pairs.
     int j = 0;
-    const int e1 = max(0, min(n_full - 1, n_act - 1)) & ~1;
-    for (; j < e1; j += 2) {
-        body(P0{}, F{}, T{}, j);
-        body(P1{}, F{}, T{}, j + 1);
+    int e1 = max(0, min(n_full - 1, n_act - 1)) & ~1;
+    // Resumable sweep: the stop word is looked at ahead of every segment boundary b that all eight
+    // wavefronts reach inside their unmasked run (and only in items whose 256 rows are all valid, so that
+    // every wavefront is in that run): requested at tile b - 8, read at tile b - 4 -- at least two barriers
+    // later -- by everyone from the same LDS word.  When it is set, the item ends at b: the loop limits
+    // shrink and the code below drains the pipeline as it does at the end of the keys.
+    int stop_b = 0x7fffffff, stop_evt = 0x7fffffff, stop_limit = 0;
+    bool stop_requested = false, stopped = false;
+    if (may_stop && p.seg_tiles >= 16 && row0 + BM <= sq) {
+        int nf0 = sk / kBN, na0 = n_tiles;
+        if (causal) {
+            nf0 = min(nf0, max(0, row0 + delta + 1) / kBN);
+            na0 = min(n_tiles, max(0, row0 + 31 + delta + kBN) / kBN);
+        }
+        stop_limit = min(max(0, min(nf0 - 1, na0 - 1)) & ~1, n_tiles - 1);
+        stop_b = p.seg_tiles;
+        if (stop_b <= stop_limit) stop_evt = (stop_b & ~1) - 8;
+    }
+    for (;;) {
+        const int e_span = min(e1, stop_evt);
+        for (; j < e_span; j += 2) {
+            body(P0{}, F{}, T{}, j);
+            body(P1{}, F{}, T{}, j + 1);
+        }
+        if (j >= e1) break;
+        if (!stop_requested) {
+            request_stop_word();
+            stop_requested = true;
+            stop_evt += 4;
+        } else if (read_stop_word() != 0) {
+            stopped = true;
+            n_tiles = n_act = n_full = stop_b;
+            e1 = max(0, stop_b - 1) & ~1;
+            stop_evt = 0x7fffffff;
+        } else {
+            stop_requested = false;
+            stop_b += p.seg_tiles;
+            stop_evt = stop_b <= stop_limit ? (stop_b & ~1) - 8 : 0x7fffffff;
+        }
     }
     if (e1 > 0) {
         // S(e1) left the unmasked run without a row maximum, and the iterations below take their
@@ -576,6 +642,9 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     }
 
     // ---- epilogue
+    if (p.progress) {   // an item stopped short keeps its fp32 state; one that is through writes the result
+        if (stopped) out_ptr = nullptr; else acc_out = nullptr;
+    }
     {
         const int row = rw0 + l32;
         const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -592,7 +661,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) x[i] = o[dt][4 * b + i] * inv;
                     const int64_t idx = obase + 32 * dt + 8 * b;
-                    if (p.acc_out) *reinterpret_cast<f32x4*>(p.acc_out + idx) = x;
+                    if (acc_out) *reinterpret_cast<f32x4*>(acc_out + idx) = x;
                     if (out_ptr) {
                         if (out_f32)
                             *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out_ptr) + idx) = x;
@@ -603,6 +672,11 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                 }
         }
     }
+    if (p.progress && threadIdx.x == 0) {
+        p.progress[logical] = stopped ? seg_done + stop_b / p.seg_tiles : kSweepDone;
+        if (!stopped) atomicSub(p.pending, 1);
+    }
+    if (stopped) return;            // a stop request: this workgroup takes no further item
     __builtin_amdgcn_s_barrier();   // every wavefront is done with the LDS stages before the next item's loads
     }   // work items of this workgroup
 }

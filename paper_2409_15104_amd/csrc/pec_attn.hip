@@ -55,9 +55,9 @@ int check_shape(const pec_shape_t* s, float* scale_out) {
     if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0) return PEC_ERR_INVALID_ARGUMENT;
     if (s->head_dim != kHeadDim) return PEC_ERR_UNSUPPORTED;
     if (s->out_dtype != PEC_BF16 && s->out_dtype != PEC_F32) return PEC_ERR_UNSUPPORTED;
-    if (s->flags & ~(uint32_t)(PEC_FLAG_SIMPLE_KERNEL | PEC_FLAG_SP_SEPARATE_MERGE | PEC_FLAG_SP_SINGLE_LAUNCH))
+    if (s->flags & ~(uint32_t)(PEC_FLAG_SIMPLE_KERNEL | PEC_FLAG_SP_SEPARATE_MERGE | PEC_FLAG_SP_STEP_LAUNCHES))
         return PEC_ERR_UNSUPPORTED;
-    if ((s->flags & PEC_FLAG_SP_SEPARATE_MERGE) && (s->flags & PEC_FLAG_SP_SINGLE_LAUNCH)) return PEC_ERR_INVALID_ARGUMENT;
+    if ((s->flags & PEC_FLAG_SP_SEPARATE_MERGE) && (s->flags & PEC_FLAG_SP_STEP_LAUNCHES)) return PEC_ERR_INVALID_ARGUMENT;
     float scale = s->scale;
     if (scale == 0.f) scale = 1.0f / std::sqrt((float)s->head_dim);
     if (!(scale > 0.f) || !std::isfinite(scale)) return PEC_ERR_INVALID_ARGUMENT;
@@ -79,9 +79,16 @@ int launch_fwd(const FwdParams& p, bool simple, hipStream_t stream) {
 }
 
 // Common body of pec_attn_chunk / pec_attn_chunk_merge.
+struct Sweep {   // resumable sweep: per-item progress table, count of unfinished items, stop word, tiles per segment
+    int32_t* progress;
+    int32_t* pending;
+    const int32_t* stop;
+    int32_t seg_tiles;
+};
+
 int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t sq, int64_t sk,
                int64_t q_off, int64_t kv_off, int causal, void* out, int out_f32, float* lse, const float* acc_in,
-               const float* lse_in, float* acc_out, int64_t lse_stride, void* stream) {
+               const float* lse_in, float* acc_out, int64_t lse_stride, void* stream, const Sweep* sweep = nullptr) {
     float scale;
     if (int rc = check_shape(shape, &scale)) return rc;
     if (sq < 0 || sk < 0) return PEC_ERR_INVALID_ARGUMENT;
@@ -114,6 +121,12 @@ int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const voi
     p.n_items = (int32_t)((sq + kBM - 1) / kBM);
     p.out_f32 = out_f32;
     p.scale_log2 = scale * kLog2e;
+    if (sweep) {
+        p.progress = sweep->progress;
+        p.pending = sweep->pending;
+        p.stop = sweep->stop;
+        p.seg_tiles = sweep->seg_tiles;
+    }
     return launch_fwd(p, (shape->flags & PEC_FLAG_SIMPLE_KERNEL) != 0, static_cast<hipStream_t>(stream));
 }
 
@@ -215,7 +228,7 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
     const __bf16* kp = static_cast<const __bf16*>(k);
     const __bf16* vp = static_cast<const __bf16*>(v);
 
-    if ((shape->flags & PEC_FLAG_SP_SINGLE_LAUNCH) || s_kv == 0)
+    if (!(shape->flags & (PEC_FLAG_SP_STEP_LAUNCHES | PEC_FLAG_SP_SEPARATE_MERGE)) || s_kv == 0)
         return chunk_impl(shape, q, k, v, s_q, s_kv, q_off, 0, causal, out, out_f32, lse, nullptr, nullptr, nullptr, s_q,
                           stream);
 
@@ -265,6 +278,44 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
         return PEC_OK;
     }
     return pec_finalize(shape, o_acc, out, s_q, stream);
+}
+
+size_t pec_sp_resumable_workspace_bytes(const pec_shape_t* shape, int64_t s_q) {
+    if (!shape || s_q <= 0 || shape->n_q_heads <= 0) return 0;
+    const size_t o = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
+    const size_t items = (size_t)((s_q + kBM - 1) / kBM) * shape->n_q_heads;
+    return o + ((items * sizeof(int32_t) + 255) & ~(size_t)255);
+}
+
+int pec_sp_prefill_resumable(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t s_q,
+                             int64_t q_off, int64_t s_kv, int64_t chunk, int causal, void* out, float* lse,
+                             void* workspace, size_t workspace_bytes, const int32_t* stop, int32_t* pending, int resume,
+                             void* stream) {
+    if (int rc = check_shape(shape, nullptr)) return rc;
+    if (shape->flags & PEC_FLAG_SIMPLE_KERNEL) return PEC_ERR_UNSUPPORTED;   // the plain kernel keeps no progress
+    if (s_q < 0 || s_kv < 0 || chunk <= 0 || q_off < 0 || !pending) return PEC_ERR_INVALID_ARGUMENT;
+    if (s_q > kMaxRows || s_kv > kMaxRows || chunk % kBN != 0 || chunk / kBN > 0x3fffffff) return PEC_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(stop) & 3u) || (reinterpret_cast<uintptr_t>(pending) & 3u)) return PEC_ERR_MISALIGNED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t items = ((s_q + kBM - 1) / kBM) * shape->n_q_heads;
+    if (s_q > 0) {
+        if (!q || !out || !lse || (s_kv > 0 && (!k || !v))) return PEC_ERR_INVALID_ARGUMENT;
+        if (misaligned(out) || misaligned(workspace)) return PEC_ERR_MISALIGNED;
+        if (!workspace || workspace_bytes < pec_sp_resumable_workspace_bytes(shape, s_q)) return PEC_ERR_WORKSPACE;
+    }
+    float* o_acc = static_cast<float*>(workspace);
+    int32_t* progress = s_q > 0 ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
+                                                             (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float))
+                                : nullptr;
+    if (!resume || s_q == 0) {
+        hipLaunchKernelGGL(sweep_init_kernel, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>((items + 255) / 256, 1024))),
+                           dim3(256), 0, st, progress, items, pending);
+        if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
+    }
+    if (s_q == 0) return PEC_OK;
+    const Sweep sweep{progress, pending, stop, (int32_t)(chunk / kBN)};
+    return chunk_impl(shape, q, k, v, s_q, s_kv, q_off, 0, causal, out, shape->out_dtype == PEC_F32, lse, o_acc, lse, o_acc,
+                      s_q, stream, &sweep);
 }
 
 int64_t pec_sp_prefill_num_steps(const pec_shape_t* shape, int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk,

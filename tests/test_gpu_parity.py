@@ -21,7 +21,8 @@ LSE_RTOL = 1e-3
 DEV = "cuda:0"
 # per-call kernel selection: the default pipelined kernel and the plain cross-check kernel
 KERNELS = [0, pec.PEC_FLAG_SIMPLE_KERNEL]
-SP_MODES = [0, pec.PEC_FLAG_SP_SEPARATE_MERGE, pec.PEC_FLAG_SP_SINGLE_LAUNCH]
+# pec_sp_prefill: the default single sweep, and the two modes that launch once per ring step
+SP_MODES = [0, pec.PEC_FLAG_SP_SEPARATE_MERGE, pec.PEC_FLAG_SP_STEP_LAUNCHES]
 
 
 @pytest.fixture(autouse=True)
@@ -242,7 +243,7 @@ def test_sp_prefill_small_config_in_full(mode, variant):
         assert_close(out, lse, o_ref[lo:hi], l_ref[:, lo:hi], "sp_prefill c1 member %d mode %d" % (r, mode))
 
 
-@pytest.mark.parametrize("mode", SP_MODES[:2])
+@pytest.mark.parametrize("mode", SP_MODES)
 def test_sp_prefill_ragged_and_noncausal(mode):
     s, hq, hkv, chunk = 1000, 4, 2, 300                         # last segment has 100 tokens
     q, k, v = synth.qkv(18, s, s, hq, hkv)
@@ -255,6 +256,132 @@ def test_sp_prefill_ragged_and_noncausal(mode):
     o_nc, l_nc = oracle.attention(q[300:600], k, v, causal=False)
     out, lse = pec.pec_sp_prefill(qd[300:600], kd, vd, 300, chunk, False, flags=mode)
     assert_close(out, lse, o_nc, l_nc, "non-causal ring")
+
+
+def _resumable_run(qd, kd, vd, q_off, chunk, causal, stop, out_dtype=torch.bfloat16, max_calls=10000, between=None):
+    """Calls pec_sp_prefill_resumable until nothing is pending; returns (out, lse, number of calls, pending after each)."""
+    s_q, hq = qd.shape[0], qd.shape[1]
+    out = torch.full((s_q, hq, 128), float("nan"), dtype=out_dtype, device=DEV)
+    lse = torch.full((hq, s_q), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(16, pec.pec_sp_resumable_workspace_bytes(qd, kd)), dtype=torch.uint8, device=DEV)
+    pending = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    history = []
+    for call in range(max_calls):
+        pec.pec_sp_prefill_resumable(qd, kd, vd, q_off, chunk, out, lse, ws, pending, stop=stop, resume=call > 0,
+                                     causal=causal)
+        history.append(int(pending.item()))
+        if history[-1] == 0:
+            return out, lse, call + 1, history
+        if between is not None:
+            between(call, ws)
+    raise AssertionError("sweep did not finish: pending %s" % history[-5:])
+
+
+RESUMABLE_CASES = [
+    # s_q, s_kv, hq, hkv, q_off, chunk, causal
+    (512, 4096, 4, 2, 3584, 1024, True),     # last member of 4 x 1024 ... with two query tiles; poll points inside
+    (512, 4096, 4, 2, 1024, 1024, True),     # an early member: two segments visible
+    (768, 5000, 2, 1, 4232, 1024, True),     # ragged key total (last segment 904 keys), three query tiles
+    (300, 4096, 2, 2, 3796, 2048, True),     # second query tile has 44 rows: only left between tiles
+    (256, 3072, 8, 2, 0, 1024, False),       # non-causal: all three segments for every row
+    (256, 2048, 2, 2, 1792, 128, True),      # segments too short to be left half way
+    (200, 0, 2, 1, 0, 1024, True),           # no keys at all
+]
+
+
+@pytest.mark.parametrize("case", RESUMABLE_CASES)
+def test_resumable_sweep_uninterrupted_and_stopped_at_every_boundary(case):
+    """The stoppable sweep against the oracle: with the stop word clear one call finishes everything; with it set from
+    the start every call takes each workgroup's first unfinished tile through exactly one more segment, so the sweep
+    is cut at every boundary it can be cut at, and the result must not depend on that."""
+    s_q, s_kv, hq, hkv, q_off, chunk, causal = case
+    q, k, v = synth.qkv(41 + s_q + s_kv, s_q, max(s_kv, 1), hq, hkv)
+    k, v = k[:s_kv], v[:s_kv]
+    o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=causal)
+    qd, kd, vd = gpu(q, k, v)
+    clear = torch.zeros(1, dtype=torch.int32, device=DEV)
+    for stop in (None, clear):
+        out, lse, calls, hist = _resumable_run(qd, kd, vd, q_off, chunk, causal, stop)
+        assert calls == 1, hist
+        assert_close(out, lse, o_ref, l_ref, "resumable %s uninterrupted" % (case,))
+    out_f, lse_f, _, _ = _resumable_run(qd, kd, vd, q_off, chunk, causal, clear, out_dtype=torch.float32)
+    assert_close(out_f, lse_f, o_ref, l_ref, "resumable %s fp32 out" % (case,))
+    raised = torch.ones(1, dtype=torch.int32, device=DEV)
+    out, lse, calls, hist = _resumable_run(qd, kd, vd, q_off, chunk, causal, raised)
+    assert_close(out, lse, o_ref, l_ref, "resumable %s stopped after every segment" % (case,))
+    assert all(a >= b for a, b in zip(hist, hist[1:])), hist          # pending never grows
+    n_tiles_q = (s_q + 255) // 256
+    assert hist[0] <= n_tiles_q * hq
+    # how many calls it must have taken: the grid holds min(items, CUs) workgroups, each leaves after one segment
+    # of one tile when that tile can be cut (256 valid rows, segments of at least 1024 keys, a boundary inside
+    # the part of the keys no row has masked) -- at least one extra call whenever some tile has two such segments
+    vis_end = min(s_kv, q_off + 256) if causal else s_kv                 # keys the first tile's first row block sees
+    if s_q >= 256 and chunk >= 1024 and vis_end // chunk >= 2:
+        assert calls >= 2, (calls, hist)
+
+
+def test_resumable_sweep_state_survives_being_copied_away_and_other_work():
+    """Between two calls the workspace and the running LSE are copied away, overwritten, and copied back while another
+    prefill runs: only that data (plus q / k / v) carries the interrupted sweep."""
+    s_q, s_kv, hq, hkv, q_off, chunk = 512, 6144, 4, 2, 5632, 1024
+    q, k, v = synth.qkv(77, s_q, s_kv, hq, hkv)
+    o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
+    qd, kd, vd = gpu(q, k, v)
+    raised = torch.ones(1, dtype=torch.int32, device=DEV)
+    out = torch.empty((s_q, hq, 128), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((hq, s_q), dtype=torch.float32, device=DEV)
+    ws = torch.empty(pec.pec_sp_resumable_workspace_bytes(qd, kd), dtype=torch.uint8, device=DEV)
+    pending = torch.zeros(1, dtype=torch.int32, device=DEV)
+    calls = 0
+    while True:
+        pec.pec_sp_prefill_resumable(qd, kd, vd, q_off, chunk, out, lse, ws, pending, stop=raised, resume=calls > 0)
+        calls += 1
+        if int(pending.item()) == 0:
+            break
+        saved_ws, saved_lse, saved_out = ws.clone(), lse.clone(), out.clone()
+        ws.fill_(0xA5), lse.fill_(float("nan")), out.fill_(float("nan"))
+        pec.pec_sp_prefill(qd[:256], kd[:512], vd[:512], 256, 256, True)      # a short request gets the GPU meanwhile
+        ws.copy_(saved_ws), lse.copy_(saved_lse), out.copy_(saved_out)
+        assert calls < 200
+    assert calls > 2
+    assert_close(out, lse, o_ref, l_ref, "resumable with state moved between calls")
+
+
+def test_resumable_sweep_stop_raised_while_the_kernel_runs():
+    """The stop word lives in pinned host memory and is raised from the host while the sweep runs; after every call
+    it is cleared, then raised again a little later.  However far each call got, the end result is the same."""
+    w = synth.WORKLOADS["c2_gqa_32k"]
+    s_q, q_off = w.chunk, w.seq - w.chunk                                  # the last member: all segments visible
+    q, k, v = synth.qkv(w.seed, w.seq, w.seq, w.n_q_heads, w.n_kv_heads)
+    qd, kd, vd = gpu(q[q_off:], k, v)
+    ref_out, ref_lse = pec.pec_sp_prefill(qd, kd, vd, q_off, w.chunk, True)
+    stop = torch.zeros(1, dtype=torch.int32).pin_memory()
+    out = torch.empty_like(ref_out)
+    lse = torch.empty_like(ref_lse)
+    ws = torch.empty(pec.pec_sp_resumable_workspace_bytes(qd, kd), dtype=torch.uint8, device=DEV)
+    pending = torch.zeros(1, dtype=torch.int32, device=DEV)
+    calls, hist = 0, []
+    while True:
+        stop[0] = 0
+        pec.pec_sp_prefill_resumable(qd, kd, vd, q_off, w.chunk, out, lse, ws, pending, stop=stop, resume=calls > 0)
+        calls += 1
+        if calls <= 3:
+            stop[0] = 1                                                    # lands somewhere inside the running kernel
+        torch.cuda.synchronize()
+        hist.append(int(pending.item()))
+        if hist[-1] == 0:
+            break
+        assert calls < 50, hist
+    # same arithmetic per tile whichever way it was cut, up to the fp32 rounding of the state that went through memory
+    assert (out.float() - ref_out.float()).abs().max().item() <= 2.0 ** -7
+    assert torch.allclose(lse, ref_lse, rtol=1e-5, atol=1e-5)
+    assert hist[0] > 0, "the first call was not interrupted: %s" % hist
+    # and against the oracle, on sampled rows of one KV group
+    rows = _edge_rows(s_q, [256, 32 * 9], 5, 24)
+    g = w.n_q_heads // w.n_kv_heads
+    heads = slice(3 * g, 4 * g)
+    o_ref, l_ref = oracle.attention(q[q_off + rows][:, heads], k[:, 3:4], v[:, 3:4], q_pos=q_off + rows, causal=True)
+    assert_close(out[rows][:, heads], lse[heads][:, rows], o_ref, l_ref, "resumable c2 sampled rows")
 
 
 @pytest.mark.parametrize("variant", KERNELS)
@@ -446,9 +573,21 @@ def test_full_size_gqa_32k_last_member_sampled_rows():
     q_off = w.seq - w.chunk
     q, k, v = synth.qkv(w.seed, w.chunk, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
     rows = synth.sample_rows(w.seed, w.chunk, boundaries=(256, 2048), n_random=24)
-    for mode in (0, pec.PEC_FLAG_SP_SINGLE_LAUNCH):
+    for mode in (0, pec.PEC_FLAG_SP_STEP_LAUNCHES):
         out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True, flags=mode)
         _sampled_check(q, k, v, out, lse, q_off, rows, what="c2 mode %d" % mode)
+
+
+def _bench_sweep(q, k, v, q_off, chunk):
+    """One ring member's prefill the way bench.py launches it: the stoppable sweep with a stop word that stays clear."""
+    out = torch.empty_like(q)
+    lse = torch.empty((q.shape[1], q.shape[0]), dtype=torch.float32, device=DEV)
+    ws = torch.empty(pec.pec_sp_resumable_workspace_bytes(q, k), dtype=torch.uint8, device=DEV)
+    stop = torch.zeros(1, dtype=torch.int32, device=DEV)
+    pending = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    pec.pec_sp_prefill_resumable(q, k, v, q_off, chunk, out, lse, ws, pending, stop=stop)
+    assert int(pending.item()) == 0
+    return out, lse
 
 
 def _edge_rows(n_rows, edges, seed, n_random):
@@ -462,7 +601,7 @@ def _edge_rows(n_rows, edges, seed, n_random):
 
 def test_full_size_gqa_128k_sampled_rows():
     """The headline shape: seq 131072 in 16 segments of 8192, launch configuration of the benchmark (one
-    pec_sp_prefill per ring member, fused merge).  Every ring member is checked on one KV head (so every KV
+    stoppable sweep per ring member; members 15 and 6 also with one launch per ring step).  Every ring member is checked on one KV head (so every KV
     head is covered twice), on rows around a 256-row workgroup edge, a 32-row wavefront edge, both ends of
     the segment and random rows; members 15, 6 and 0 additionally on a second KV head."""
     w = synth.WORKLOADS["c3_gqa_128k"]
@@ -471,7 +610,11 @@ def test_full_size_gqa_128k_sampled_rows():
     for r in range(n_members):
         q_off = r * w.chunk
         q = q_all[q_off:q_off + w.chunk]
-        out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
+        out, lse = _bench_sweep(q, k, v, q_off, w.chunk)
+        if r in (15, 6):
+            out_s, lse_s = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True, flags=pec.PEC_FLAG_SP_STEP_LAUNCHES)
+            assert (out_s.float() - out.float()).abs().max().item() <= 2.0 ** -7
+            assert torch.allclose(lse_s, lse, rtol=1e-5, atol=1e-5)
         wg_edge = 256 * (1 + (5 * r) % 31)            # a workgroup (256-row) edge, different for every member
         wave_edge = wg_edge + 32 * (1 + r % 7)        # a wavefront (32-row) edge inside the next workgroup
         rows = _edge_rows(w.chunk, (wg_edge, wave_edge), w.seed + r, 4)
@@ -507,7 +650,7 @@ def test_full_size_gqa_512k_last_member_sampled_rows():
     w = synth.WORKLOADS["c5_gqa_512k"]
     q_off = w.seq - w.chunk
     q, k, v = synth.qkv(w.seed, w.chunk, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
-    out, lse = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True)
+    out, lse = _bench_sweep(q, k, v, q_off, w.chunk)
     for kvh, wg_edge, wave_edge in ((3, 256 * 17, 256 * 40 + 96), (0, 256 * 1, 256 * 63 + 32), (6, 256 * 50, 256 * 9 + 224)):
         rows = _edge_rows(w.chunk, (wg_edge, wave_edge), w.seed + kvh, 2)
         _sampled_check(q, k, v, out, lse, q_off, rows, heads=kvh, what="c5 last member kv head %d" % kvh)
@@ -529,7 +672,7 @@ def test_resumable_prefill_states_match_oracle_and_survive_preemption():
         n = pec.pec_sp_prefill_num_steps(qd, kd, lo, chunk)
         assert n == r + 1
         states = oracle.sp_prefill_states(q_all[lo:hi], k, v, q_off=lo, chunk=chunk, causal=True)
-        ref_out, ref_lse = pec.pec_sp_prefill(qd, kd, vd, lo, chunk, True)
+        ref_out, ref_lse = pec.pec_sp_prefill(qd, kd, vd, lo, chunk, True, flags=pec.PEC_FLAG_SP_STEP_LAUNCHES)
         o_acc = torch.full((hi - lo, hq, 128), float("nan"), dtype=torch.float32, device=DEV)   # step 0 must not read it
         l_acc = torch.full((hq, hi - lo), float("nan"), dtype=torch.float32, device=DEV)
         out = torch.empty((hi - lo, hq, 128), dtype=torch.bfloat16, device=DEV)

@@ -46,10 +46,10 @@ def test_unknown_or_contradictory_flags_are_refused(lib):
     call = lambda flags: lib.pec_attn_chunk(ctypes.byref(S(8, 2, 128, 0, 0.0, flags)), fake, fake, fake, 0, 16, 0, 0, 1,  # noqa: E731
                                             fake, fake, None)
     for flags in (0, binding.PEC_FLAG_SIMPLE_KERNEL, binding.PEC_FLAG_SP_SEPARATE_MERGE,
-                  binding.PEC_FLAG_SIMPLE_KERNEL | binding.PEC_FLAG_SP_SINGLE_LAUNCH):
+                  binding.PEC_FLAG_SIMPLE_KERNEL | binding.PEC_FLAG_SP_STEP_LAUNCHES):
         assert call(flags) == 0                      # sq = 0: accepted, nothing launched
     assert call(8) == -2 and call(1 << 31) == -2     # unknown bits
-    assert call(binding.PEC_FLAG_SP_SEPARATE_MERGE | binding.PEC_FLAG_SP_SINGLE_LAUNCH) == -1
+    assert call(binding.PEC_FLAG_SP_SEPARATE_MERGE | binding.PEC_FLAG_SP_STEP_LAUNCHES) == -1
 
 
 def test_argument_validation_happens_on_the_host(lib):
@@ -72,8 +72,9 @@ def test_argument_validation_happens_on_the_host(lib):
     assert lib.pec_attn_merge(ctypes.byref(ok), None, fake, fake, fake, 4, None) == -1
     assert lib.pec_attn_merge(ctypes.byref(ok), fake, fake, fake, fake, 0, None) == 0
     assert lib.pec_finalize(ctypes.byref(ok), fake, odd, 4, None) == -3
-    # sp_prefill: several segments need a workspace
-    assert lib.pec_sp_prefill(ctypes.byref(ok), fake, fake, fake, 64, 64, 128, 64, 1, fake, fake, None, 0, None) == -4
+    # sp_prefill, one launch per ring step: several segments need a workspace
+    steps = S(8, 2, 128, binding.PEC_BF16, 0.0, binding.PEC_FLAG_SP_STEP_LAUNCHES)
+    assert lib.pec_sp_prefill(ctypes.byref(steps), fake, fake, fake, 64, 64, 128, 64, 1, fake, fake, None, 0, None) == -4
     assert lib.pec_sp_prefill(ctypes.byref(ok), fake, fake, fake, 64, 0, 128, 0, 1, fake, fake, fake, 1 << 30, None) == -1
     need = lib.pec_sp_workspace_bytes(ctypes.byref(ok), 64)
     assert need >= 2 * 64 * 8 * 128 * 4 + 64 * 8 * 4
@@ -90,6 +91,18 @@ def test_argument_validation_happens_on_the_host(lib):
     assert coloc(ok, cq=None) == -1
     assert coloc(S(8, 2, 128, 0, 0.0, binding.PEC_FLAG_SIMPLE_KERNEL)) == -2
     assert coloc(ok, batch=0) == 0
+    # resumable sweep: pending is required, chunk a multiple of 64, no plain kernel, workspace checked
+    need = lib.pec_sp_resumable_workspace_bytes(ctypes.byref(ok), 512)
+    assert need >= 512 * 8 * 128 * 4 + 2 * 8 * 4
+    sweep = lambda shp=ok, chunk=1024, ws=fake, nbytes=1 << 40, pending=fake, stop=fake: lib.pec_sp_prefill_resumable(  # noqa: E731
+        ctypes.byref(shp), fake, fake, fake, 512, 0, 4096, chunk, 1, fake, fake, ws, nbytes, stop, pending, 0, None)
+    assert sweep(pending=None) == -1
+    assert sweep(chunk=1000) == -2
+    assert sweep(chunk=0) == -1
+    assert sweep(S(8, 2, 128, 0, 0.0, binding.PEC_FLAG_SIMPLE_KERNEL)) == -2
+    assert sweep(nbytes=need - 1) == -4
+    assert sweep(ws=None) == -4
+    assert sweep(stop=ctypes.c_void_p(0x1002)) == -3 and sweep(pending=ctypes.c_void_p(0x1002)) == -3
 
 
 def test_binding_refuses_cpu_tensors(lib):
