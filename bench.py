@@ -7,7 +7,7 @@ order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c5_gqa_512k|c4_varlen|c4_colocated|decode_512k|ulysses_layout]
-                  [--sp-mode fused|separate|single] [--simple-kernel] [--share] [--no-cpu-baseline]
+                  [--sp-mode resumable|sweep|step|separate] [--simple-kernel] [--share] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -139,7 +139,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3_gqa_128k")
-    ap.add_argument("--sp-mode", default="fused", choices=["fused", "separate", "single"])
+    ap.add_argument("--sp-mode", default="resumable", choices=["resumable", "sweep", "step", "separate"],
+                    help="resumable: one stoppable sweep launch per ring member, stop word polled and never set (default); "
+                         "sweep: the same launch without a stop word; step: one launch per ring step, merge fused; "
+                         "separate: one launch per ring step plus a merge kernel")
     ap.add_argument("--simple-kernel", action="store_true", help="time the plain cross-check kernel instead of the default")
     ap.add_argument("--share", action="store_true",
                     help="time one GPU's share only: the last ring member's prefill (its query segment against all KV segments)")
@@ -188,8 +191,10 @@ def main():
     if args.mfma_probe:
         print(json.dumps({"mfma_probe": mfma_probe(torch, pec, dev), "nominal_peak_tflops": PEAK_BF16_TFLOPS}), flush=True)
         return 0
-    mode = {"fused": 0, "separate": pec.PEC_FLAG_SP_SEPARATE_MERGE, "single": pec.PEC_FLAG_SP_SINGLE_LAUNCH}[args.sp_mode]
     args.kernel_flag = pec.PEC_FLAG_SIMPLE_KERNEL if args.simple_kernel else 0
+    if args.simple_kernel and args.sp_mode == "resumable":
+        args.sp_mode = "sweep"          # the plain kernel keeps no progress table
+    mode = {"resumable": 0, "sweep": 0, "step": pec.PEC_FLAG_SP_STEP_LAUNCHES, "separate": pec.PEC_FLAG_SP_SEPARATE_MERGE}[args.sp_mode]
     args.flags = mode | args.kernel_flag
 
     if args.workload == "c4_varlen":
@@ -209,24 +214,34 @@ def main():
     q, k, v = synth.qkv(w.seed, S, S, Hq, Hkv, device=dev)
     out = torch.empty_like(q)
     lse = torch.empty((P, Hq, C), dtype=torch.float32, device=dev)   # one [Hq, C] block per ring member
-    ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C)), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C), pec.pec_sp_resumable_workspace_bytes(q[:C], k)),
+                     dtype=torch.uint8, device=dev)
+    stop = torch.zeros(1, dtype=torch.int32, device=dev)        # the scheduler's stop word: never raised here
+    pending = torch.zeros(P, dtype=torch.int32, device=dev)
 
     pairs = sum(synth.visible_pairs(C, min(C, S - c * C), r * C, c * C, True)
                 for r in range(P) for c in range(r + 1))
     assert pairs == S * (S + 1) // 2
     flops = FLOP_PER_PAIR * Hq * pairs
-    launches = P * (P + 1) // 2 if mode != pec.PEC_FLAG_SP_SINGLE_LAUNCH else P
+    launches = P * (P + 1) // 2 if mode else P
 
     def step():
         for r in range(P):
             lo = r * C
-            pec.pec_sp_prefill(q[lo:lo + C], k, v, lo, C, True, out=out[lo:lo + C], lse=lse[r], workspace=ws, flags=args.flags)
+            if args.sp_mode == "resumable":
+                pec.pec_sp_prefill_resumable(q[lo:lo + C], k, v, lo, C, out[lo:lo + C], lse[r], ws, pending[r:r + 1], stop=stop)
+            else:
+                pec.pec_sp_prefill(q[lo:lo + C], k, v, lo, C, True, out=out[lo:lo + C], lse=lse[r], workspace=ws,
+                                   flags=args.flags)
 
     ms_step, ev_ms = timed_steps(torch, step, args.steps, args.warmup)
+    if args.sp_mode == "resumable" and int(pending.abs().sum().item()) != 0:
+        print("bench.py: a sweep did not run to its end: pending %s" % pending.tolist(), file=sys.stderr)
+        return 1
     ev_ms_step = sum(ev_ms) / len(ev_ms)
     tflops = flops / (ms_step * 1e-3) / 1e12
 
-    # Dominant kernel = the attention kernel (every launch of the timed region in fused/single mode).
+    # Dominant kernel = the attention kernel (every launch of the timed region except in separate mode).
     # Average launch duration from HIP events on the launch stream over the timed region.
     avg_launch_ms = ev_ms_step / launches
     achieved = (flops / launches) / (avg_launch_ms * 1e-3) / 1e12
@@ -268,13 +283,19 @@ def bench_share(args, torch, pec, synth, dev, w, mode):
     q, k, v = synth.qkv(w.seed, C, S, Hq, Hkv, device=dev)      # Q of the one segment only
     out = torch.empty_like(q)
     lse = torch.empty((Hq, C), dtype=torch.float32, device=dev)
-    ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C)), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(16, pec.pec_sp_workspace_bytes(Hq, Hkv, C), pec.pec_sp_resumable_workspace_bytes(q, k)),
+                     dtype=torch.uint8, device=dev)
+    stop = torch.zeros(1, dtype=torch.int32, device=dev)
+    pending = torch.zeros(1, dtype=torch.int32, device=dev)
     lo = S - C
     flops = FLOP_PER_PAIR * Hq * synth.visible_pairs(C, S, lo, 0, True)
-    launches = P if mode != pec.PEC_FLAG_SP_SINGLE_LAUNCH else 1
+    launches = P if mode else 1
 
     def step():
-        pec.pec_sp_prefill(q, k, v, lo, C, True, out=out, lse=lse, workspace=ws, flags=args.flags)
+        if args.sp_mode == "resumable":
+            pec.pec_sp_prefill_resumable(q, k, v, lo, C, out, lse, ws, pending, stop=stop)
+        else:
+            pec.pec_sp_prefill(q, k, v, lo, C, True, out=out, lse=lse, workspace=ws, flags=args.flags)
 
     ms_step, ev_list = timed_steps(torch, step, args.steps, args.warmup)
     ev_mean = sum(ev_list) / len(ev_list)
