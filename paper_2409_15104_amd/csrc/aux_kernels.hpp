@@ -250,6 +250,7 @@ __global__ __launch_bounds__(1024) void build_worklist_kernel(const int32_t* __r
     block_suffix_sum_1024(bucket, n_t + 1, red);                   // bucket[t] = sequences with more than t tiles
     const int total = block_suffix_sum_1024(bucket, n_t, red);     // bucket[t] = list position of the first item of tile t
     if (tid == 0) *n_work = min(total, capacity);
+    if (tid >= 8 && tid < 16) n_work[tid] = 0;   // the attention kernel's draw counters, one per XCD
     // placement: one wavefront per sequence, one lane per tile
     const int wave = tid >> 6, lane = tid & 63;
     for (int b = wave; b < batch; b += 16) {
@@ -328,6 +329,7 @@ __global__ __launch_bounds__(1024) void build_colocated_worklist_kernel(
     // bucket[w] <- number of items heavier than w = list position of the first item of weight w
     const int total = block_suffix_sum_1024(bucket, n_buckets, red);
     if (tid == 0) counters[0] = min(total, capacity);
+    if (tid >= 8 && tid < 16) counters[tid] = 0;   // the attention kernel's draw counters, one per XCD
     for (int b = wave; b < batch; b += 16) {
         const Seq s = seq_of(b);
         if (seq_slot0[b] == -2) continue;

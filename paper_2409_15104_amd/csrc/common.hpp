@@ -66,6 +66,8 @@ struct FwdParams {
     const int32_t* cu_seqlens;
     const WorkItem* work;
     const int32_t* n_work;  // number of valid work items
+    int32_t* sched;         // eight zeroed counters (fwd_il_kernel only): work items are drawn from them, one
+                            // counter per XCD's share of the work order, instead of being dealt in fixed rounds
     int32_t total_tokens;   // rows of the packed arrays (bounds every index taken from cu_seqlens)
     // split-KV mode (kv_split_len > 0; fwd_il_kernel only): work item = key range
     // [item * kv_split_len, ...), partial results go to out / lse + item * split_*_stride

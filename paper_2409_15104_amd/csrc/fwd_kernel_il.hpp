@@ -58,7 +58,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     // of the tile loop is then "lane offset + 16-bit immediate".  (Separate arrays are placed by the
     // compiler in an order of its own; a stage that lands above 64 KiB needs its address in a register,
     // and the tile loop has none to spare.)
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_all[4 * kTileBytes + 256];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_all[4 * kTileBytes + 256 + 64];
     unsigned char* const lds_k0 = lds_all;
     unsigned char* const lds_k1 = lds_all + kTileBytes;
     unsigned char* const lds_v0 = lds_all + 2 * kTileBytes;
@@ -66,9 +66,14 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
 
     // ---- persistent workgroups: the grid holds n_slots workgroups per XCD (hardware deals block
     // ids round-robin over the 8 XCDs); each XCD owns one contiguous logical range of the
-    // (KV-head-major, longest-rows-first) work order and its workgroups walk it in snake order
-    // (slot, then reversed slot, ...), which evens out the causal length differences.
-    const int64_t total = (int64_t)p.n_items * p.n_q_heads;
+    // (KV-head-major, longest-rows-first) work order.  Dense calls: its workgroups walk it in snake order
+    // (slot, then reversed slot, ...), which evens out the causal length differences.  Work-list calls
+    // (p.sched): items differ in length by orders of magnitude and the XCDs do not run at the same speed, so
+    // every workgroup draws its next item from its XCD's counter, and from the next XCD's once that share is
+    // used up; the heaviest items come first in the list, so the launch ends on the lightest ones.
+    const bool dynamic = p.sched != nullptr;
+    const int n_items_eff = dynamic ? min(*p.n_work, p.n_items) : p.n_items;
+    const int64_t total = (int64_t)n_items_eff * p.n_q_heads;
     const int64_t per_xcd = (total + 7) >> 3;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_slots = (int)(gridDim.x >> 3);
@@ -85,11 +90,45 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         }
     };
     auto read_stop_word = [&]() -> int {
-        const int v = *reinterpret_cast<const volatile int*>(lds_all + 4 * kTileBytes);
+        const int v = *(const __attribute__((address_space(3))) volatile int*)(lds_all + 4 * kTileBytes);
         return __builtin_amdgcn_readfirstlane(v);
     };
     bool first_item = true;   // of this workgroup in this launch: it is never abandoned before its first segment
-    for (int64_t round0 = 0; round0 < per_xcd; round0 += n_slots) {
+    // Drawing (work-list calls): lane 0 of wavefront 0 takes the next index and leaves it in one of two LDS
+    // words used in turn; everyone reads it after the next barrier.  The draw for item i + 1 is made while item
+    // i waits for its first tiles, so its latency is hidden; only the first draw, and the one after an index
+    // that turns out to hold no work, is waited for.  Words 2 and 3 (lane 0's own): the XCD share being drawn
+    // from and how many shares were found used up.
+    typedef __attribute__((address_space(3))) volatile int lds_int;
+    lds_int* const lds_sched = (lds_int*)(lds_all + 4 * kTileBytes + 256);
+    int sched_par = 0;         // which of the two words holds the index to take next
+    bool have_next = false;
+    auto draw_next = [&](int into) {
+        if (wave == 0) {
+            int ln;
+            asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln));
+            if (ln == 0) {
+                int x = lds_sched[2], t = lds_sched[3], got = -1;
+                while (t < 8) {
+                    const int v = atomicAdd(&p.sched[x], 1);
+                    if (v < per_xcd && (int64_t)x * per_xcd + v < total) {
+                        got = (int)(x * per_xcd + v);
+                        break;
+                    }
+                    x = (x + 1) & 7;
+                    ++t;
+                }
+                lds_sched[into] = got;
+                lds_sched[2] = x;
+                lds_sched[3] = t;
+            }
+        }
+    };
+    if (dynamic && threadIdx.x == 0) {
+        lds_sched[2] = (int)(blockIdx.x & 7);
+        lds_sched[3] = 0;
+    }
+    for (int64_t round0 = 0; dynamic || round0 < per_xcd; round0 += n_slots) {
     // Lane-derived values are recomputed for every work item (the empty asm hides that they are
     // loop invariant): hoisted out of this loop they would stay live through the tile loop, which
     // has no register to spare -- a spill reload there waits on the tile loads just issued.
@@ -97,11 +136,24 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
     const int l32 = lane & 31;
     const int hl = lane >> 5;
-    const int64_t idx_in_xcd = round0 + (((round0 / n_slots) & 1) ? (n_slots - 1 - slot) : slot);
-    if (idx_in_xcd >= per_xcd) continue;
-    const int64_t logical = (int64_t)(blockIdx.x & 7) * per_xcd + idx_in_xcd;
-    if (logical >= total) continue;
-    const int per_kvh = p.n_items * p.group;
+    int64_t logical;
+    if (dynamic) {
+        if (!have_next) {
+            draw_next(sched_par);
+            __builtin_amdgcn_s_barrier();
+        }
+        have_next = false;
+        const int got = __builtin_amdgcn_readfirstlane(lds_sched[sched_par]);
+        sched_par ^= 1;
+        if (got < 0) break;
+        logical = got;
+    } else {
+        const int64_t idx_in_xcd = round0 + (((round0 / n_slots) & 1) ? (n_slots - 1 - slot) : slot);
+        if (idx_in_xcd >= per_xcd) continue;
+        logical = (int64_t)(blockIdx.x & 7) * per_xcd + idx_in_xcd;
+        if (logical >= total) continue;
+    }
+    const int per_kvh = n_items_eff * p.group;
     const int kvh = (int)(logical / per_kvh);
     const int rem = (int)(logical % per_kvh);
     const int item = rem / p.group;
@@ -548,6 +600,10 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     issue_v(0, lds_v1);
     const bool may_stop = p.stop != nullptr;
     if (may_stop && !first_item) request_stop_word();
+    if (dynamic) {   // the next item's index, while this one waits for its first tiles
+        draw_next(sched_par);
+        have_next = true;
+    }
     end_of_iteration();
     if (may_stop && !first_item && read_stop_word() != 0) return;   // nothing of this item has been touched
     first_item = false;

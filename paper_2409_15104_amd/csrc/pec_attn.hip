@@ -620,6 +620,7 @@ int pec_attn_varlen(const pec_shape_t* shape, const void* q, const void* k, cons
     p.cu_seqlens = cu_seqlens;
     p.work = work;
     p.n_work = n_work;
+    p.sched = n_work + 8;   // same 256-byte block, zeroed by the builder
     p.total_tokens = (int32_t)total_tokens;
     return launch_fwd(p, (shape->flags & PEC_FLAG_SIMPLE_KERNEL) != 0, st);
 }
@@ -704,6 +705,7 @@ int pec_attn_colocated(const pec_shape_t* shape, const void* q, const void* k, c
     p.cu_seqlens = cu_seqlens_q;
     p.work = work;
     p.n_work = counters;
+    p.sched = counters + 8;   // same 256-byte block, zeroed by the builder
     p.total_tokens = (int32_t)total_q;
     p.cu_seqlens_k = cu_seqlens_k;
     p.seq_slot0 = seq_slot0;
