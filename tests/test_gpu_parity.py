@@ -615,6 +615,12 @@ def test_full_size_gqa_128k_sampled_rows():
             out_s, lse_s = pec.pec_sp_prefill(q, k, v, q_off, w.chunk, True, flags=pec.PEC_FLAG_SP_STEP_LAUNCHES)
             assert (out_s.float() - out.float()).abs().max().item() <= 2.0 ** -7
             assert torch.allclose(lse_s, lse, rtol=1e-5, atol=1e-5)
+        if r == 15:     # the same member cut at every segment boundary (stop word set throughout), then continued
+            raised = torch.ones(1, dtype=torch.int32, device=DEV)
+            out_c, lse_c, calls, hist = _resumable_run(q, k, v, q_off, w.chunk, True, raised)
+            assert calls >= 16 and all(a >= b for a, b in zip(hist, hist[1:])), (calls, hist[:8])
+            assert (out_c.float() - out.float()).abs().max().item() <= 2.0 ** -7
+            assert torch.allclose(lse_c, lse, rtol=1e-5, atol=1e-5)
         wg_edge = 256 * (1 + (5 * r) % 31)            # a workgroup (256-row) edge, different for every member
         wave_edge = wg_edge + 32 * (1 + r % 7)        # a wavefront (32-row) edge inside the next workgroup
         rows = _edge_rows(w.chunk, (wg_edge, wave_edge), w.seed + r, 4)
