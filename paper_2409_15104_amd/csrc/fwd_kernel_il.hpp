@@ -217,7 +217,10 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         lse_off0 = (int64_t)head * p.lse_stride;
         if (p.progress) {           // resumable sweep: continue behind the segments already folded in
             seg_done = p.progress[logical];
-            if (seg_done == kSweepDone) continue;
+            // (a table that was never initialised must not send the loads out of bounds: anything that is
+            // not a count of segments inside the key range is taken as "through" or as "not started")
+            if (seg_done == kSweepDone || (seg_done > 0 && (int64_t)seg_done * p.seg_tiles * kBN >= (int64_t)sk)) continue;
+            seg_done = max(seg_done, 0);
             if (seg_done == 0) acc_in = nullptr;
             kv_tok0 = (int64_t)seg_done * p.seg_tiles * kBN;
             sk -= (int)kv_tok0;
