@@ -142,8 +142,9 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  * that have not yet seen their last key (0: out and lse are complete).  A launch
  * always takes each workgroup's first unfinished tile through at least one more
  * segment, so repeated calls end even if *stop stays set.
- *   stop    : int32 the GPU can read while the kernel runs (device memory written from
- *             another stream, or pinned host memory); NULL = never stop.  Segments
+ *   stop    : int32 the GPU can read while the kernel runs: pinned host memory written by the
+ *             host, or device memory written by a copy or a kernel on another stream (it is
+ *             read past the caches); NULL = never stop.  Segments
  *             shorter than 1024 keys, and query tiles with fewer than 256 rows, are
  *             only left between tiles, not between segments.
  *   pending : DEVICE int32, written by the call (resume = 0 sets it to the tile count).

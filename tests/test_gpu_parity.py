@@ -347,25 +347,44 @@ def test_resumable_sweep_state_survives_being_copied_away_and_other_work():
     assert_close(out, lse, o_ref, l_ref, "resumable with state moved between calls")
 
 
-def test_resumable_sweep_stop_raised_while_the_kernel_runs():
-    """The stop word lives in pinned host memory and is raised from the host while the sweep runs; after every call
-    it is cleared, then raised again a little later.  However far each call got, the end result is the same."""
-    w = synth.WORKLOADS["c2_gqa_32k"]
-    s_q, q_off = w.chunk, w.seq - w.chunk                                  # the last member: all segments visible
-    q, k, v = synth.qkv(w.seed, w.seq, w.seq, w.n_q_heads, w.n_kv_heads)
-    qd, kd, vd = gpu(q[q_off:], k, v)
+@pytest.mark.parametrize("where", ["pinned host word", "device word, copy on a side stream", "device word, kernel on a side stream"])
+def test_resumable_sweep_stop_raised_while_the_kernel_runs(where):
+    """The stop word is raised while the sweep runs -- by the host in pinned memory, or in device memory by a copy or
+    a fill kernel on another stream; after every call it is cleared, then raised again a little later.  However
+    far each call got, the end result is the same."""
+    w = synth.WORKLOADS["c3_gqa_128k"]                                     # the last member's sweep runs ~14 ms
+    s_q, q_off = w.chunk, w.seq - w.chunk
+    qd, kd, vd = synth.qkv(w.seed + 7, s_q, w.seq, w.n_q_heads, w.n_kv_heads, device=DEV)
     ref_out, ref_lse = pec.pec_sp_prefill(qd, kd, vd, q_off, w.chunk, True)
-    stop = torch.zeros(1, dtype=torch.int32).pin_memory()
+    pinned = where.startswith("pinned")
+    stop = torch.zeros(1, dtype=torch.int32).pin_memory() if pinned else torch.zeros(1, dtype=torch.int32, device=DEV)
+    one = torch.ones(1, dtype=torch.int32).pin_memory()
+    side = torch.cuda.Stream()
     out = torch.empty_like(ref_out)
     lse = torch.empty_like(ref_lse)
     ws = torch.empty(pec.pec_sp_resumable_workspace_bytes(qd, kd), dtype=torch.uint8, device=DEV)
     pending = torch.zeros(1, dtype=torch.int32, device=DEV)
     calls, hist = 0, []
     while True:
-        stop[0] = 0
+        raise_it = calls < 3
+        if pinned:
+            stop[0] = 0
+        else:
+            stop.zero_()
+            torch.cuda.synchronize()
+            if raise_it:    # queued up front: the side stream starts with the sweep, idles ~1 ms, then raises the word
+                start = torch.cuda.Event()
+                start.record()
+                side.wait_event(start)
+                with torch.cuda.stream(side):
+                    torch.cuda._sleep(2000000)
+                    if "copy" in where:
+                        stop.copy_(one, non_blocking=True)
+                    else:
+                        stop.fill_(1)
         pec.pec_sp_prefill_resumable(qd, kd, vd, q_off, w.chunk, out, lse, ws, pending, stop=stop, resume=calls > 0)
         calls += 1
-        if calls <= 3:
+        if pinned and raise_it:
             stop[0] = 1                                                    # lands somewhere inside the running kernel
         torch.cuda.synchronize()
         hist.append(int(pending.item()))
@@ -377,11 +396,7 @@ def test_resumable_sweep_stop_raised_while_the_kernel_runs():
     assert torch.allclose(lse, ref_lse, rtol=1e-5, atol=1e-5)
     assert hist[0] > 0, "the first call was not interrupted: %s" % hist
     # and against the oracle, on sampled rows of one KV group
-    rows = _edge_rows(s_q, [256, 32 * 9], 5, 24)
-    g = w.n_q_heads // w.n_kv_heads
-    heads = slice(3 * g, 4 * g)
-    o_ref, l_ref = oracle.attention(q[q_off + rows][:, heads], k[:, 3:4], v[:, 3:4], q_pos=q_off + rows, causal=True)
-    assert_close(out[rows][:, heads], lse[heads][:, rows], o_ref, l_ref, "resumable c2 sampled rows")
+    _sampled_check(qd, kd, vd, out, lse, q_off, _edge_rows(s_q, [256, 32 * 9], 5, 6), heads=3, what="resumable c3 " + where)
 
 
 @pytest.mark.parametrize("variant", KERNELS)
