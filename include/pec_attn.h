@@ -141,7 +141,12 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  * tile from where it stopped; *pending is then the number of query tiles x heads
  * that have not yet seen their last key (0: out and lse are complete).  A launch
  * always takes each workgroup's first unfinished tile through at least one more
- * segment, so repeated calls end even if *stop stays set.
+ * segment, so repeated calls end even if *stop stays set.  A stopped tile's state
+ * is stored as the kernel held it (un-normalised O, softmax reference, partial
+ * denominators), so a stop adds no rounding step: the result equals the
+ * uninterrupted sweep's bit for bit, except that a row with a score, within two
+ * tiles of a cut, more than 2^8 above its running softmax reference may differ by
+ * one fp32 rescale.
  *   stop    : int32 the GPU can read while the kernel runs: pinned host memory written by the
  *             host, or device memory written by a copy or a kernel on another stream (it is
  *             read past the caches); NULL = never stop.  Segments
@@ -151,8 +156,8 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  *   resume  : 0 starts from the first segment and ignores the workspace contents.
  *   chunk   : a multiple of 64 (PEC_ERR_UNSUPPORTED otherwise).
  *   workspace: pec_sp_resumable_workspace_bytes() bytes, 16-byte aligned; holds the
- *             state between calls (the caller may copy it away and back); lse holds
- *             the running LSE of unfinished tiles meanwhile.
+ *             state between calls (the caller may copy it away and back, together
+ *             with lse, which holds part of the state of unfinished tiles meanwhile).
  * PEC_FLAG_SIMPLE_KERNEL is refused (PEC_ERR_UNSUPPORTED).
  */
 int pec_sp_prefill_resumable(const pec_shape_t* shape, const void* q, const void* k, const void* v,

@@ -88,9 +88,12 @@ struct FwdParams {
     int32_t coloc_range_len;    // keys per range, a multiple of 64
     // resumable sweep (dense mode, progress != null; fwd_il_kernel only): work item i has finished its first
     // progress[i] key segments of seg_tiles tiles each (kSweepDone: all of them) and continues from there, its
-    // running pair in acc_in / lse_in.  A nonzero *stop makes a workgroup end the item in hand at the next
-    // segment boundary (state to acc_out / lse, progress updated) and take no further item; an item that gets
-    // through its last key writes out / lse and takes one off *pending.
+    // running state in acc_in / lse_in / l_part.  A nonzero *stop makes a workgroup end the item in hand at the next
+    // segment boundary (state to acc_out / lse / l_part, progress updated) and take no further item; an item that
+    // gets through its last key writes out / lse and takes one off *pending.  The state of a stopped item is kept
+    // as the registers hold it -- un-normalised O, the softmax reference (log2 units) in the LSE slot, and the two
+    // lane halves' partial denominators in l_part [n_q_heads][lse_stride][2] -- so a stop adds no rounding step.
+    float* l_part;
     int32_t* progress;
     int32_t* pending;
     const int32_t* stop;

@@ -50,7 +50,16 @@ __device__ __forceinline__ void scale_acc_in_place(f32x16 (&o)[4], float a) {
         for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(o[dt][r]) : "v"(a));
 }
 
+// Three instances, so that each carries only its own bookkeeping through the (register-starved) work-item code:
+// kFwdDense -- one call = one problem, work items dealt in fixed rounds (ring step, fused merge, key splits, the
+// plain sweep); kFwdSweep -- the resumable sweep (progress table, stop word, state of stopped items);
+// kFwdList -- device-built work lists (packed and colocated batch), work items drawn at run time.
+enum { kFwdDense = 0, kFwdSweep = 1, kFwdList = 2 };
+
+template <int MODE>
 __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
+    constexpr bool kSweep = MODE == kFwdSweep;
+    constexpr bool kList = MODE == kFwdList;
     constexpr int NWAVES = 8;
     constexpr int BM = NWAVES * 32;
 
@@ -71,7 +80,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     // (p.sched): items differ in length by orders of magnitude and the XCDs do not run at the same speed, so
     // every workgroup draws its next item from its XCD's counter, and from the next XCD's once that share is
     // used up; the heaviest items come first in the list, so the launch ends on the lightest ones.
-    const bool dynamic = p.sched != nullptr;
+    constexpr bool dynamic = kList;
     const int n_items_eff = dynamic ? min(*p.n_work, p.n_items) : p.n_items;
     const int64_t total = (int64_t)n_items_eff * p.n_q_heads;
     const int64_t per_xcd = (total + 7) >> 3;
@@ -170,7 +179,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     const float* acc_in = p.acc_in;
     float* acc_out = p.acc_out;
     int seg_done = 0;          // resumable sweep: key segments this item has behind it
-    if (p.cu_seqlens) {
+    if constexpr (kList) {
         if (item >= *p.n_work) continue;
         const WorkItem w = p.work[item];
         const int b0 = min(max(p.cu_seqlens[w.seq], 0), p.total_tokens);
@@ -215,7 +224,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         q_off0 = (int64_t)head * (p.q_head_stride ? p.q_head_stride : kHeadDim);
         o_off0 = q_off0;
         lse_off0 = (int64_t)head * p.lse_stride;
-        if (p.progress) {           // resumable sweep: continue behind the segments already folded in
+        if constexpr (kSweep) {     // continue behind the segments already folded in
             seg_done = p.progress[logical];
             // (a table that was never initialised must not send the loads out of bounds: anything that is
             // not a count of segments inside the key range is taken as "through" or as "not started")
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
             sk -= (int)kv_tok0;
             delta -= (int)kv_tok0;
         }
-        if (p.kv_split_len > 0) {   // the work item is a key range; all of it is visible (decode)
+        if (!kSweep && p.kv_split_len > 0) {   // the work item is a key range; all of it is visible (decode)
             qt = 0;
             kv_tok0 = (int64_t)item * p.kv_split_len;
             sk = (int)max((int64_t)0, min((int64_t)p.kv_split_len, (int64_t)p.sk - kv_tok0));
@@ -285,9 +294,10 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
         const int row = rw0 + l32;
         if (row < sq) {
             const float lin = p.lse_in[lse_off0 + row];
-            if (lin != -INFINITY) {
-                m_run = lin * kLog2e;
-                l_run = hl == 0 ? 1.f : 0.f;
+            constexpr bool raw = kSweep;   // state of a stopped sweep item, stored as the registers held it
+            if (raw || lin != -INFINITY) {
+                m_run = raw ? lin : lin * kLog2e;
+                l_run = raw ? p.l_part[(lse_off0 + row) * 2 + hl] : (hl == 0 ? 1.f : 0.f);
                 const float* arow = acc_in + o_off0 + row * q_stride + 4 * hl;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
@@ -601,7 +611,7 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     issue_k(0, lds_k0);
     issue_k(1, lds_k1);
     issue_v(0, lds_v1);
-    const bool may_stop = p.stop != nullptr;
+    const bool may_stop = kSweep && p.stop != nullptr;
     if (may_stop && !first_item) request_stop_word();
     if (dynamic) {   // the next item's index, while this one waits for its first tiles
         draw_next(sched_par);
@@ -701,15 +711,17 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
     }
 
     // ---- epilogue
-    if (p.progress) {   // an item stopped short keeps its fp32 state; one that is through writes the result
+    if constexpr (kSweep) {   // an item stopped short keeps its fp32 state; one that is through writes the result
         if (stopped) out_ptr = nullptr; else acc_out = nullptr;
     }
     {
         const int row = rw0 + l32;
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         if (row < sq) {
-            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-            const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+            const bool raw = kSweep && stopped;   // a stopped sweep item keeps its state as it stands
+            const float inv = raw ? 1.f : (l_tot > 0.f ? 1.f / l_tot : 0.f);
+            const float lse = raw ? m_run : (l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY);
+            if (raw) p.l_part[(lse_off0 + row) * 2 + hl] = l_run;
             if (hl == 0) lse_ptr[lse_off0 + row] = lse;
             const int64_t obase = o_off0 + row * q_stride + 4 * hl;
 #pragma unroll
@@ -731,11 +743,11 @@ __global__ __launch_bounds__(512) void fwd_il_kernel(const FwdParams p) {
                 }
         }
     }
-    if (p.progress && threadIdx.x == 0) {
+    if (kSweep && threadIdx.x == 0) {
         p.progress[logical] = stopped ? seg_done + stop_b / p.seg_tiles : kSweepDone;
         if (!stopped) atomicSub(p.pending, 1);
     }
-    if (stopped) return;            // a stop request: this workgroup takes no further item
+    if (kSweep && stopped) return;  // a stop request: this workgroup takes no further item
     __builtin_amdgcn_s_barrier();   // every wavefront is done with the LDS stages before the next item's loads
     }   // work items of this workgroup
 }

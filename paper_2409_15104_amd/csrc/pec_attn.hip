@@ -38,7 +38,12 @@ int compute_units() {
 void launch_il(const FwdParams& p, unsigned grid, hipStream_t st) {
     const unsigned per_xcd = grid / 8;
     const unsigned slots = std::max(1u, std::min(per_xcd, (unsigned)compute_units() / 8));
-    hipLaunchKernelGGL(fwd_il_kernel, dim3(8 * slots), dim3(512), 0, st, p);
+    if (p.progress)
+        hipLaunchKernelGGL(fwd_il_kernel<kFwdSweep>, dim3(8 * slots), dim3(512), 0, st, p);
+    else if (p.cu_seqlens)
+        hipLaunchKernelGGL(fwd_il_kernel<kFwdList>, dim3(8 * slots), dim3(512), 0, st, p);
+    else
+        hipLaunchKernelGGL(fwd_il_kernel<kFwdDense>, dim3(8 * slots), dim3(512), 0, st, p);
 }
 
 // Both kernels take 256 query rows per workgroup, so work lists and launch geometry do not depend
@@ -80,6 +85,7 @@ int launch_fwd(const FwdParams& p, bool simple, hipStream_t stream) {
 
 // Common body of pec_attn_chunk / pec_attn_chunk_merge.
 struct Sweep {   // resumable sweep: per-item progress table, count of unfinished items, stop word, tiles per segment
+    float* l_part;
     int32_t* progress;
     int32_t* pending;
     const int32_t* stop;
@@ -122,6 +128,7 @@ int chunk_impl(const pec_shape_t* shape, const void* q, const void* k, const voi
     p.out_f32 = out_f32;
     p.scale_log2 = scale * kLog2e;
     if (sweep) {
+        p.l_part = sweep->l_part;
         p.progress = sweep->progress;
         p.pending = sweep->pending;
         p.stop = sweep->stop;
@@ -282,9 +289,11 @@ int pec_sp_prefill(const pec_shape_t* shape, const void* q, const void* k, const
 
 size_t pec_sp_resumable_workspace_bytes(const pec_shape_t* shape, int64_t s_q) {
     if (!shape || s_q <= 0 || shape->n_q_heads <= 0) return 0;
+    // un-normalised fp32 O, two partial denominators per (head, row), progress table
     const size_t o = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
+    const size_t l = (((size_t)s_q * shape->n_q_heads * 2 * sizeof(float)) + 255) & ~(size_t)255;
     const size_t items = (size_t)((s_q + kBM - 1) / kBM) * shape->n_q_heads;
-    return o + ((items * sizeof(int32_t) + 255) & ~(size_t)255);
+    return o + l + ((items * sizeof(int32_t) + 255) & ~(size_t)255);
 }
 
 int pec_sp_prefill_resumable(const pec_shape_t* shape, const void* q, const void* k, const void* v, int64_t s_q,
@@ -304,16 +313,17 @@ int pec_sp_prefill_resumable(const pec_shape_t* shape, const void* q, const void
         if (!workspace || workspace_bytes < pec_sp_resumable_workspace_bytes(shape, s_q)) return PEC_ERR_WORKSPACE;
     }
     float* o_acc = static_cast<float*>(workspace);
-    int32_t* progress = s_q > 0 ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
-                                                             (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float))
-                                : nullptr;
+    const size_t o_bytes = (size_t)s_q * shape->n_q_heads * kHeadDim * sizeof(float);
+    const size_t l_bytes = (((size_t)s_q * shape->n_q_heads * 2 * sizeof(float)) + 255) & ~(size_t)255;
+    float* l_part = s_q > 0 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + o_bytes) : nullptr;
+    int32_t* progress = s_q > 0 ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + o_bytes + l_bytes) : nullptr;
     if (!resume || s_q == 0) {
         hipLaunchKernelGGL(sweep_init_kernel, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>((items + 255) / 256, 1024))),
                            dim3(256), 0, st, progress, items, pending);
         if (hipGetLastError() != hipSuccess) return PEC_ERR_HIP;
     }
     if (s_q == 0) return PEC_OK;
-    const Sweep sweep{progress, pending, stop, (int32_t)(chunk / kBN)};
+    const Sweep sweep{l_part, progress, pending, stop, (int32_t)(chunk / kBN)};
     return chunk_impl(shape, q, k, v, s_q, s_kv, q_off, 0, causal, out, shape->out_dtype == PEC_F32, lse, o_acc, lse, o_acc,
                       s_q, stream, &sweep);
 }

@@ -306,9 +306,13 @@ def test_resumable_sweep_uninterrupted_and_stopped_at_every_boundary(case):
         assert_close(out, lse, o_ref, l_ref, "resumable %s uninterrupted" % (case,))
     out_f, lse_f, _, _ = _resumable_run(qd, kd, vd, q_off, chunk, causal, clear, out_dtype=torch.float32)
     assert_close(out_f, lse_f, o_ref, l_ref, "resumable %s fp32 out" % (case,))
+    out_u, lse_u = out, lse
     raised = torch.ones(1, dtype=torch.int32, device=DEV)
     out, lse, calls, hist = _resumable_run(qd, kd, vd, q_off, chunk, causal, raised)
     assert_close(out, lse, o_ref, l_ref, "resumable %s stopped after every segment" % (case,))
+    # a stopped tile keeps its state exactly as the registers held it, so on such data (no score near a cut far
+    # above the running softmax reference) the cuts do not change a single bit
+    assert torch.equal(out, out_u) and torch.equal(lse, lse_u), "cuts changed the result of %s" % (case,)
     assert all(a >= b for a, b in zip(hist, hist[1:])), hist          # pending never grows
     n_tiles_q = (s_q + 255) // 256
     assert hist[0] <= n_tiles_q * hq
@@ -391,9 +395,8 @@ def test_resumable_sweep_stop_raised_while_the_kernel_runs(where):
         if hist[-1] == 0:
             break
         assert calls < 50, hist
-    # same arithmetic per tile whichever way it was cut, up to the fp32 rounding of the state that went through memory
-    assert (out.float() - ref_out.float()).abs().max().item() <= 2.0 ** -7
-    assert torch.allclose(lse, ref_lse, rtol=1e-5, atol=1e-5)
+    # same arithmetic per tile wherever it was cut, and the state goes through memory as the registers held it
+    assert torch.equal(out, ref_out) and torch.equal(lse, ref_lse)
     assert hist[0] > 0, "the first call was not interrupted: %s" % hist
     # and against the oracle, on sampled rows of one KV group
     _sampled_check(qd, kd, vd, out, lse, q_off, _edge_rows(s_q, [256, 32 * 9], 5, 6), heads=3, what="resumable c3 " + where)
@@ -634,8 +637,7 @@ def test_full_size_gqa_128k_sampled_rows():
             raised = torch.ones(1, dtype=torch.int32, device=DEV)
             out_c, lse_c, calls, hist = _resumable_run(q, k, v, q_off, w.chunk, True, raised)
             assert calls >= 16 and all(a >= b for a, b in zip(hist, hist[1:])), (calls, hist[:8])
-            assert (out_c.float() - out.float()).abs().max().item() <= 2.0 ** -7
-            assert torch.allclose(lse_c, lse, rtol=1e-5, atol=1e-5)
+            assert torch.equal(out_c, out) and torch.equal(lse_c, lse)
         wg_edge = 256 * (1 + (5 * r) % 31)            # a workgroup (256-row) edge, different for every member
         wave_edge = wg_edge + 32 * (1 + r % 7)        # a wavefront (32-row) edge inside the next workgroup
         rows = _edge_rows(w.chunk, (wg_edge, wave_edge), w.seed + r, 4)
