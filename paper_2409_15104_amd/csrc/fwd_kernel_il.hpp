@@ -21,8 +21,8 @@
 // 256 B row, so the global access stays fully coalesced); 8 wavefronts x 32 query rows; one
 // workgroup barrier per tile.
 //
-// LDS: two stages each for K and V (four arrays; every access names its array because the
-// loop is unrolled by two).  Iteration j, parity
+// LDS: two stages each for K and V (four 16 KiB pieces of one block; every access names its stage because
+// the loop is unrolled by two).  Iteration j, parity
 // r = j % 2: loads K(j+2) -> K[r] and V(j) -> V[r]; reads K(j+1) from K[1-r] and V(j-1)
 // from V[1-r].
 #pragma once
