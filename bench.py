@@ -224,6 +224,11 @@ def main():
     assert pairs == S * (S + 1) // 2
     flops = FLOP_PER_PAIR * Hq * pairs
     launches = P * (P + 1) // 2 if mode else P
+    how = {"resumable": "one stoppable sweep launch per ring member, the segments' partial results merged by the online "
+                        "softmax in registers, stop word polled at every segment boundary",
+           "sweep": "one sweep launch per ring member, the segments' partial results merged in registers",
+           "step": "one launch per ring step, LSE merge fused into the next step's kernel",
+           "separate": "one launch per ring step, LSE merge by a separate kernel"}[args.sp_mode]
 
     def step():
         for r in range(P):
@@ -256,7 +261,7 @@ def main():
         "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: causal prefill, %d q heads / %d kv heads, d 128, seq %d as %d segments of %d, "
-                               "full ring sweep with LSE merge (%s)" % (w.name, Hq, Hkv, S, P, C, args.sp_mode),
+                               "full ring sweep with LSE merge (%s)" % (w.name, Hq, Hkv, S, P, C, how),
                    "seq_len": S, "chunk": C, "n_q_heads": Hq, "n_kv_heads": Hkv, "sp_mode": args.sp_mode,
                    "kernel": pec.KERNEL_NAMES[args.kernel_flag]},
         "tokens_per_s": round(S / (ms_step * 1e-3), 1),
