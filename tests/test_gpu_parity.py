@@ -368,7 +368,7 @@ def test_resumable_sweep_stop_raised_while_the_kernel_runs(where):
     lse = torch.empty_like(ref_lse)
     ws = torch.empty(pec.pec_sp_resumable_workspace_bytes(qd, kd), dtype=torch.uint8, device=DEV)
     pending = torch.zeros(1, dtype=torch.int32, device=DEV)
-    calls, hist = 0, []
+    calls, hist, fresh, sweeps = 0, [], True, 1
     while True:
         raise_it = calls < 3
         if pinned:
@@ -386,18 +386,21 @@ def test_resumable_sweep_stop_raised_while_the_kernel_runs(where):
                         stop.copy_(one, non_blocking=True)
                     else:
                         stop.fill_(1)
-        pec.pec_sp_prefill_resumable(qd, kd, vd, q_off, w.chunk, out, lse, ws, pending, stop=stop, resume=calls > 0)
-        calls += 1
+        pec.pec_sp_prefill_resumable(qd, kd, vd, q_off, w.chunk, out, lse, ws, pending, stop=stop, resume=not fresh)
+        calls, fresh = calls + 1, False
         if pinned and raise_it:
             stop[0] = 1                                                    # lands somewhere inside the running kernel
         torch.cuda.synchronize()
         hist.append(int(pending.item()))
         if hist[-1] == 0:
-            break
+            if max(hist) > 0 or sweeps == 3:
+                break
+            # the host was held up for the whole 14 ms of the kernel: nothing was interrupted, so start over
+            calls, hist, fresh, sweeps = 0, [], True, sweeps + 1
         assert calls < 50, hist
     # same arithmetic per tile wherever it was cut, and the state goes through memory as the registers held it
     assert torch.equal(out, ref_out) and torch.equal(lse, ref_lse)
-    assert hist[0] > 0, "the first call was not interrupted: %s" % hist
+    assert max(hist) > 0, "no call was interrupted in three sweeps: %s" % hist
     # and against the oracle, on sampled rows of one KV group
     _sampled_check(qd, kd, vd, out, lse, q_off, _edge_rows(s_q, [256, 32 * 9], 5, 6), heads=3, what="resumable c3 " + where)
 
