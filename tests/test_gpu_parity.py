@@ -286,6 +286,9 @@ RESUMABLE_CASES = [
     (256, 3072, 8, 2, 0, 1024, False),       # non-causal: all three segments for every row
     (256, 2048, 2, 2, 1792, 128, True),      # segments too short to be left half way
     (200, 0, 2, 1, 0, 1024, True),           # no keys at all
+    (2048, 6144, 2, 2, 4096, 1024, True),    # the query segment spans two key segments: tiles end in different ones
+    (256, 3000, 4, 2, 0, 1024, False),       # non-causal with a short last segment (952 keys)
+    (512, 4096, 16, 2, 3584, 2048, True),    # groups of 8 query heads per KV head
 ]
 
 
