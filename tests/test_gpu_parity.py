@@ -327,6 +327,25 @@ def test_resumable_sweep_uninterrupted_and_stopped_at_every_boundary(case):
         assert calls >= 2, (calls, hist)
 
 
+def test_resumable_sweep_with_jumps_of_the_row_maximum_around_the_cuts():
+    """Keys that lift single rows' scores 16 ... 130 log2 units above the bulk, placed in the last two tiles before a
+    segment boundary (the tiles a stopped item drains through), on the boundary itself and right behind it (the first
+    tile of the continued item): the softmax reference has to follow on both sides of every cut.  Here cut and
+    uninterrupted sweeps may differ in the rounding of single rows, so both are held to the oracle, not to each other."""
+    s_q, s_kv, hq, hkv, q_off, chunk = 256, 4096, 8, 2, 3840, 1024
+    outliers = [(896, 3, 2), (960, 40, 8), (1023, 77, 4), (1024, 100, 8), (1025, 101, 1), (1088, 130, 2),
+                (2047, 180, 8), (2048, 181, 8), (3008, 200, 4), (3071, 220, 1), (3072, 221, 8), (3073, 255, 2),
+                (3100, 0, 8), (4000, 250, 8)]
+    q, k, v = synth.qkv_with_outlier_keys(4545, s_q, s_kv, hq, hkv, outliers)
+    o_ref, l_ref = oracle.attention(q, k, v, q_off=q_off, kv_off=0, causal=True)
+    qd, kd, vd = gpu(q, k, v)
+    for stop_value, what in ((0, "uninterrupted"), (1, "cut at every boundary")):
+        stop = torch.full((1,), stop_value, dtype=torch.int32, device=DEV)
+        out, lse, calls, hist = _resumable_run(qd, kd, vd, q_off, chunk, True, stop, out_dtype=torch.float32)
+        assert calls == (1 if stop_value == 0 else 4), hist
+        assert_close(out, lse, o_ref, l_ref, "outlier keys around the cuts, " + what)
+
+
 def test_resumable_sweep_state_survives_being_copied_away_and_other_work():
     """Between two calls the workspace and the running LSE are copied away, overwritten, and copied back while another
     prefill runs: only that data (plus q / k / v) carries the interrupted sweep."""
