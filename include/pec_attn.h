@@ -135,7 +135,7 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  * long prefill yields at operation granularity and only the intermediate data of
  * the interrupted operation is kept).  Every workgroup looks at *stop shortly
  * before each segment boundary of the query tile it is working on; once it reads a
- * nonzero value it finishes the segment in hand, puts the tile's running fp32 pair
+ * nonzero value it finishes the segment in hand, puts the tile's running state
  * and the number of segments done into the workspace, and takes no further tile.
  * A later call with resume = 1 and the same arguments and workspace continues every
  * tile from where it stopped; *pending is then the number of query tiles x heads
@@ -158,7 +158,8 @@ size_t pec_sp_workspace_bytes(const pec_shape_t* shape, int64_t s_q);
  *   workspace: pec_sp_resumable_workspace_bytes() bytes, 16-byte aligned; holds the
  *             state between calls (the caller may copy it away and back, together
  *             with lse, which holds part of the state of unfinished tiles meanwhile).
- * PEC_FLAG_SIMPLE_KERNEL is refused (PEC_ERR_UNSUPPORTED).
+ * PEC_FLAG_SIMPLE_KERNEL is refused (PEC_ERR_UNSUPPORTED).  Two calls that use one
+ * workspace at the same time race; one sweep needs one workspace.
  */
 int pec_sp_prefill_resumable(const pec_shape_t* shape, const void* q, const void* k, const void* v,
                              int64_t s_q, int64_t q_off, int64_t s_kv, int64_t chunk, int causal,
