@@ -6,7 +6,7 @@ segment r = 0..P-1 runs pec_sp_prefill over the KV segments it can see, in ring
 order, with the log-sum-exp merge folded in at every step.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c5_gqa_512k|c4_varlen|c4_colocated|decode_512k|ulysses_layout]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_gqa_128k|c2_gqa_32k|c1_mha_2k|c5_gqa_512k|c4_varlen|c4_colocated|c3_preempt|decode_512k|ulysses_layout]
                   [--sp-mode resumable|sweep|step|separate] [--simple-kernel] [--share] [--no-cpu-baseline]
 """
 from __future__ import annotations
@@ -201,6 +201,8 @@ def main():
         return bench_varlen(args, torch, np, pec, synth, dev)
     if args.workload == "c4_colocated":
         return bench_colocated(args, torch, np, pec, synth, dev)
+    if args.workload == "c3_preempt":
+        return bench_preempt(args, torch, np, pec, synth, dev)
     if args.workload.startswith("decode"):
         return bench_decode(args, torch, np, pec, synth, dev)
     if args.workload.startswith("ulysses"):
@@ -450,6 +452,84 @@ def bench_colocated(args, torch, np, pec, synth, dev):
         "roofline": {"bound": "mfma", "achieved": round(flops / (ev_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(flops / (ev_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": "pec::fwd_il_kernel"},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_preempt(args, torch, np, pec, synth, dev):
+    """Stopping and continuing a long prefill (section "Preemption of Long-Request Prefill"): the last c3 ring member's
+    sweep (8192 query rows against 131072 keys in 16 segments) with the stop word, in pinned host memory, raised by
+    the host some milliseconds into the kernel.  Reported: how long after the word is raised the host sees the kernel
+    gone from the GPU, and what the stop and the continuation cost on top of the uninterrupted sweep."""
+    import time
+
+    w = synth.WORKLOADS["c3_gqa_128k"]
+    S, C, Hq, Hkv = w.seq, w.chunk, w.n_q_heads, w.n_kv_heads
+    lo = S - C
+    q, k, v = synth.qkv(w.seed, C, S, Hq, Hkv, device=dev)
+    out = torch.empty_like(q)
+    lse = torch.empty((Hq, C), dtype=torch.float32, device=dev)
+    ws = torch.empty(pec.pec_sp_resumable_workspace_bytes(q, k), dtype=torch.uint8, device=dev)
+    stop = torch.zeros(1, dtype=torch.int32).pin_memory()
+    pending = torch.zeros(1, dtype=torch.int32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)   # noqa: E731
+
+    def sweep(resume):
+        pec.pec_sp_prefill_resumable(q, k, v, lo, C, out, lse, ws, pending, stop=stop, resume=resume)
+
+    _, ev_full = timed_steps(torch, lambda: sweep(False), args.steps, args.warmup)
+    full_ms = sorted(ev_full)[len(ev_full) // 2]
+    latencies, overheads, left = [], [], []
+    trials = max(args.steps, 10)
+    for t in range(trials):
+        stop[0] = 0
+        torch.cuda.synchronize()
+        delay_s = (0.15 + 0.7 * t / max(1, trials - 1)) * full_ms * 1e-3      # 15 ... 85 % into the kernel
+        e0, e1, e2, e3 = ev(), ev(), ev(), ev()
+        e0.record()
+        sweep(False)
+        e1.record()
+        t_launch = time.perf_counter()
+        while time.perf_counter() - t_launch < delay_s:
+            pass
+        stop[0] = 1
+        t_raise = time.perf_counter()
+        while not e1.query():
+            pass
+        t_gone = time.perf_counter()
+        torch.cuda.synchronize()
+        n_left = int(pending.item())
+        if n_left == 0:
+            continue                      # the kernel was through before the word was raised
+        stop[0] = 0
+        e2.record()
+        sweep(True)
+        e3.record()
+        torch.cuda.synchronize()
+        if int(pending.item()) != 0:
+            print("bench.py: the continued sweep did not finish", file=sys.stderr)
+            return 1
+        latencies.append(1e3 * (t_gone - t_raise))
+        overheads.append(e0.elapsed_time(e1) + e2.elapsed_time(e3) - full_ms)
+        left.append(n_left)
+    if not latencies:
+        print("bench.py: no sweep was interrupted", file=sys.stderr)
+        return 1
+    items_per_cu = max(1, (C // 256) * Hq // 256)
+    result = {
+        "metric": "time from raising the stop word to the prefill kernel having left the GPU (seen from the host)",
+        "value": round(step_stats(latencies)["median"], 4),
+        "unit": "ms", "n_gpus": 1, "steps": len(latencies), "warmup": args.warmup, "ms_per_step": round(full_ms, 3),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3_preempt: last ring member of c3_gqa_128k (8192 query rows, 131072 keys in 16 segments), one "
+                               "stoppable sweep launch, stop word in pinned host memory raised by the host 15 ... 85 % into it, "
+                               "then continued to the end"},
+        "stop_latency_ms": step_stats(latencies),
+        "one_key_segment_of_one_query_tile_ms": round(full_ms / (S // C) / items_per_cu, 4),
+        "stop_and_continue_overhead_ms": step_stats(overheads),
+        "uninterrupted_sweep_ms": round(full_ms, 3),
+        "work_items_left_at_stop": {"min": min(left), "max": max(left), "of": (C // 256) * Hq},
     }
     print(json.dumps(result), flush=True)
     return 0
