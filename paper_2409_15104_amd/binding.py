@@ -212,9 +212,10 @@ def pec_sp_prefill(q, k, v, q_off: int, chunk: int, causal: bool = True, out_dty
     if lse is None:
         lse = torch.empty((hq, s_q), dtype=torch.float32, device=q.device)
     shp = _shape(q, k, out_dtype, scale, flags)
-    if workspace is None:
-        workspace = torch.empty(max(16, int(lib().pec_sp_workspace_bytes(ctypes.byref(shp), s_q))), dtype=torch.uint8,
-                                device=q.device)
+    if workspace is None:   # only the modes that launch once per ring step keep state between launches
+        per_step = flags & (PEC_FLAG_SP_STEP_LAUNCHES | PEC_FLAG_SP_SEPARATE_MERGE)
+        nbytes = int(lib().pec_sp_workspace_bytes(ctypes.byref(shp), s_q)) if per_step else 0
+        workspace = torch.empty(max(16, nbytes), dtype=torch.uint8, device=q.device)
     _check("pec_sp_prefill",
            lib().pec_sp_prefill(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(v), s_q, int(q_off), s_kv, int(chunk),
                                 int(bool(causal)), _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(),
